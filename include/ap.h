@@ -1,0 +1,139 @@
+/*
+ * ap.h -- C ABI of the MI355X (gfx950) masked-attention library for Attention Pruning (AP).
+ *
+ * AP fixes one global sparseness mask per (layer, head): entries of the attention matrix
+ * whose dataset-averaged weight falls below a percentile threshold are pruned (paper,
+ * Section 3.2, Eq. (1) and Eq. (2)), and attention is then computed as
+ *
+ *     A~ = softmax( (Q K^T + M_p) / sqrt(d_k) ) V              (Section 3.2, masked equation)
+ *
+ * with M_p = 0 on kept entries and -infinity on pruned ones.  The mask has no batch index.
+ * This library evaluates that expression only where the mask is set.
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - The caller owns every buffer.  The library allocates and frees nothing and keeps no
+ *     state between calls.
+ *   - Every call enqueues work on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and returns without synchronising.
+ *   - Errors are return codes; nothing throws or aborts.  Arguments are validated on the
+ *     host before anything is launched, so a call that returns AP_ERR_INVALID_ARG or
+ *     AP_ERR_UNSUPPORTED has touched no device memory.
+ *   - Results are deterministic: the layout is bit-identical from run to run, and O is
+ *     bitwise reproducible for fixed inputs (fixed tile order, no atomics).
+ */
+#ifndef AP_H
+#define AP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ap_status {
+    AP_OK = 0,
+    AP_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, misaligned pointer or stride, ...  */
+    AP_ERR_UNSUPPORTED = -2, /* valid request outside what the kernels implement (D, tile shape)   */
+    AP_ERR_CAPACITY = -3,    /* a caller-provided buffer is smaller than the stated requirement     */
+    AP_ERR_HIP = -4          /* the HIP runtime refused a launch or no GPU is present               */
+} ap_status;
+
+typedef enum ap_dtype {
+    AP_F32 = 0, /* IEEE binary32 in and out, fp32 arithmetic                                        */
+    AP_BF16 = 1 /* bfloat16 in and out, bf16 matrix-core products with fp32 accumulation            */
+} ap_dtype;
+
+/* Human-readable name of a status code (host pointer to a static string). */
+const char *ap_status_string(ap_status s);
+
+/* ---------------------------------------------------------------------------------------------
+ * Layout: element mask -> block-sparse layout.
+ *
+ * The paper's hardware section (Section 9.2) runs AP on block-sparse kernels, i.e. the mask of
+ * Eq. (2) is organised in blocks.  Here a block ("tile") is block_m query rows by block_n key
+ * columns, and each stored tile carries the element bitmap of its window, so the element
+ * mask of Eq. (2) is represented exactly rather than rounded to blocks.
+ *
+ *   nQB = ceil(Lq / block_m), nKB = ceil(Lk / block_n), W = ceil(block_n / 64).
+ *   A tile (h, qb, kb) is stored iff any mask byte inside its window (clipped to Lq x Lk) is
+ *   nonzero.  Block rows are numbered r = h * nQB + qb.
+ *
+ *   row_ptr [H*nQB + 1]  int32   exclusive prefix sum of stored tiles per block row; row_ptr[0] = 0
+ *   col_idx [nnz]        int32   kb of each stored tile, ascending inside a block row
+ *   bitmaps [nnz*block_m*W] uint64  word (t, rr, w): bit c%64 of word w = c/64 is
+ *                                mask[h, qb*block_m + rr, kb*block_n + c] != 0; bits whose
+ *                                row or column lies outside the mask are 0
+ *
+ * Supported: block_m in {16, 32, 64, 128}, block_n in {16, 32, 64, 128}; H*nQB*nKB < 2^31.
+ * ------------------------------------------------------------------------------------------- */
+
+/* Upper bound H*nQB*nKB on the number of stored tiles (so buffers can be sized without a
+ * device round trip).  Returns -1 for invalid arguments. */
+int64_t ap_layout_max_tiles(int H, int Lq, int Lk, int block_m, int block_n);
+
+/* Bytes of device scratch that ap_build_layout needs for these sizes (0 for invalid arguments). */
+size_t ap_layout_workspace_bytes(int H, int Lq, int Lk, int block_m, int block_n);
+
+/*
+ * Build the layout of `mask` (uint8 [H, Lq, Lk], row-major, any nonzero byte = kept).
+ *
+ *   row_ptr      out, int32 [H*nQB + 1]
+ *   col_idx      out, int32 [cap]; may be NULL together with bitmaps to obtain only row_ptr
+ *                and nnz_out (count-only use: read nnz_out, allocate exactly, call again)
+ *   bitmaps      out, uint64 [cap * block_m * W], 8-byte aligned
+ *   cap          number of tiles col_idx/bitmaps have room for.  Tiles whose position is
+ *                >= cap are counted but not written: the call stays asynchronous, so the
+ *                caller compares *nnz_out with cap after synchronising.  Passing
+ *                cap >= ap_layout_max_tiles(...) can never truncate.
+ *   nnz_out      out, device int64: total number of stored tiles (= row_ptr[H*nQB]); may be NULL
+ *   workspace    device scratch of at least ap_layout_workspace_bytes(...) bytes, 8-byte aligned;
+ *                contents are undefined afterwards
+ *
+ * Returns AP_ERR_CAPACITY if workspace_bytes is too small, AP_ERR_INVALID_ARG / AP_ERR_UNSUPPORTED
+ * for bad sizes or pointers, AP_ERR_HIP if a launch fails.
+ */
+ap_status ap_build_layout(const uint8_t *mask, int H, int Lq, int Lk, int block_m, int block_n,
+                          int32_t *row_ptr, int32_t *col_idx, uint64_t *bitmaps, int64_t cap,
+                          int64_t *nnz_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Masked attention forward (Section 3.2, masked-attention equation).
+ *
+ * For every batch b, head h and query i, over the keys j with mask[h,i,j] != 0 (and, if
+ * `causal`, j <= i + (Lk - Lq): the auto-regressive mask composes with the pruning mask):
+ *
+ *     s_ij = scale * <Q[b,h,i,:], K[b,h,j,:]>
+ *     lse[b,h,i] = ln sum_j exp(s_ij)
+ *     O[b,h,i,:] = sum_j exp(s_ij - lse[b,h,i]) * V[b,h,j,:]
+ *
+ * A query with no visible kept key gets O = 0 and lse = -infinity.
+ *
+ *   Q, O          [B, H, Lq, D]; K, V  [B, H, Lk, D]; element type `dtype`; the last dimension
+ *                 is contiguous; stride_x = {batch, head, sequence} strides in ELEMENTS (host
+ *                 pointers to 3 int64).  Base pointers and row starts must be 16-byte aligned
+ *                 (strides multiples of 8 elements for bf16, 4 for fp32).  O must not alias
+ *                 Q, K or V.  Inputs must be finite: a pruned key's value row is still
+ *                 multiplied by an exact zero inside a visited tile.
+ *   lse           out, float [B, H, Lq] contiguous, or NULL
+ *   row_ptr, col_idx, bitmaps   layout from ap_build_layout with the same H, Lq, Lk, block_m,
+ *                 block_n; read-only, reusable across any number of calls
+ *   causal        nonzero = also hide future keys; requires Lk >= Lq
+ *   softmax_scale <= 0 selects 1/sqrt(D)
+ *
+ * Supported: D in {32, 64, 128}; block_n = 64; block_m = 64 (both dtypes) or 128 (bf16).
+ * Returns AP_ERR_UNSUPPORTED otherwise.
+ * ------------------------------------------------------------------------------------------- */
+ap_status ap_sparse_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *lse,
+                             ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                             const int64_t *stride_q, const int64_t *stride_k,
+                             const int64_t *stride_v, const int64_t *stride_o,
+                             const int32_t *row_ptr, const int32_t *col_idx,
+                             const uint64_t *bitmaps, int block_m, int block_n,
+                             int causal, float softmax_scale, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AP_H */

@@ -1,0 +1,180 @@
+"""Thin ctypes binding of the C ABI in include/ap.h (same names, argument marshalling only).
+
+PyTorch supplies device memory and the HIP stream; every step of the computation runs in the
+library's own kernels.  There is no fallback: if the shared library has not been built, the
+first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple, Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libap_mi355x.so")
+
+AP_OK = 0
+AP_ERR_INVALID_ARG = -1
+AP_ERR_UNSUPPORTED = -2
+AP_ERR_CAPACITY = -3
+AP_ERR_HIP = -4
+AP_F32 = 0
+AP_BF16 = 1
+
+SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
+           "ap_build_layout", "ap_sparse_attn_fwd")
+
+_lib = None
+
+
+class ApError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, ap_status_string(status), status))
+
+
+def lib() -> ctypes.CDLL:
+    """Load libap_mi355x.so (built by ``python -m paper_2012_02030_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "HIP library %s is missing: build it with `python -m paper_2012_02030_amd.build` "
+                "(there is no CPU fallback)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+        L.ap_status_string.restype = ctypes.c_char_p
+        L.ap_status_string.argtypes = [i32]
+        L.ap_layout_max_tiles.restype = i64
+        L.ap_layout_max_tiles.argtypes = [i32] * 5
+        L.ap_layout_workspace_bytes.restype = ctypes.c_size_t
+        L.ap_layout_workspace_bytes.argtypes = [i32] * 5
+        L.ap_build_layout.restype = i32
+        L.ap_build_layout.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp,
+                                      ctypes.c_size_t, vp]
+        L.ap_sparse_attn_fwd.restype = i32
+        L.ap_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                         ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                         ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                         vp, vp, vp, i32, i32, i32, ctypes.c_float, vp]
+        _lib = L
+    return _lib
+
+
+def ap_status_string(status: int) -> str:
+    return lib().ap_status_string(int(status)).decode()
+
+
+def ap_layout_max_tiles(H: int, Lq: int, Lk: int, block_m: int, block_n: int) -> int:
+    return int(lib().ap_layout_max_tiles(H, Lq, Lk, block_m, block_n))
+
+
+def ap_layout_workspace_bytes(H: int, Lq: int, Lk: int, block_m: int, block_n: int) -> int:
+    return int(lib().ap_layout_workspace_bytes(H, Lq, Lk, block_m, block_n))
+
+
+class Layout(NamedTuple):
+    """Device arrays of a block-sparse layout plus the sizes it was built for."""
+    row_ptr: torch.Tensor    # int32 [H*nQB + 1]
+    col_idx: torch.Tensor    # int32 [cap]
+    bitmaps: torch.Tensor    # int64 storage of uint64 words [cap, block_m, ceil(block_n/64)]
+    nnz: torch.Tensor        # int64 [1] on device
+    H: int
+    Lq: int
+    Lk: int
+    block_m: int
+    block_n: int
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def ap_build_layout(mask: torch.Tensor, block_m: int = 64, block_n: int = 64,
+                    cap: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None,
+                    count_only: bool = False) -> Layout:
+    """mask: uint8/bool device tensor [H, Lq, Lk], nonzero = kept.  Asynchronous on the stream."""
+    if mask.dtype == torch.bool:
+        mask = mask.view(torch.uint8)
+    if mask.dtype != torch.uint8 or mask.dim() != 3 or not mask.is_cuda:
+        raise ValueError("mask must be a uint8/bool device tensor [H, Lq, Lk]")
+    mask = mask.contiguous()
+    H, Lq, Lk = mask.shape
+    max_tiles = ap_layout_max_tiles(H, Lq, Lk, block_m, block_n)
+    if max_tiles < 0:
+        raise ApError(AP_ERR_UNSUPPORTED, "ap_layout_max_tiles")
+    if cap is None:
+        cap = max_tiles
+    dev = mask.device
+    nqb = -(-Lq // block_m)
+    W = -(-block_n // 64)
+    row_ptr = torch.empty(H * nqb + 1, dtype=torch.int32, device=dev)
+    nnz = torch.empty(1, dtype=torch.int64, device=dev)
+    ws_bytes = ap_layout_workspace_bytes(H, Lq, Lk, block_m, block_n)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    if count_only:
+        col_idx = torch.empty(0, dtype=torch.int32, device=dev)
+        bitmaps = torch.empty((0, block_m, W), dtype=torch.int64, device=dev)
+        cptr = bptr = None
+    else:
+        col_idx = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+        bitmaps = torch.empty((max(cap, 1), block_m, W), dtype=torch.int64, device=dev)
+        cptr, bptr = col_idx.data_ptr(), bitmaps.data_ptr()
+    st = lib().ap_build_layout(mask.data_ptr(), H, Lq, Lk, block_m, block_n, row_ptr.data_ptr(),
+                               cptr, bptr, cap, nnz.data_ptr(), ws.data_ptr(), ws_bytes,
+                               _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_build_layout")
+    # ws is released to torch's caching allocator here; the allocator is stream-ordered, so the
+    # kernels enqueued above finish with it before any later allocation on this stream reuses it
+    return Layout(row_ptr, col_idx, bitmaps, nnz, H, Lq, Lk, block_m, block_n)
+
+
+def _strides3(t: torch.Tensor):
+    return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
+def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout: Layout,
+                       causal: bool = False, softmax_scale: float = 0.0,
+                       out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                       return_lse: bool = True, stream: Optional[torch.cuda.Stream] = None):
+    """Q [B,H,Lq,D], K/V [B,H,Lk,D] device tensors (fp32 or bf16, last dim contiguous).
+
+    Returns (O, lse); lse is None when return_lse is False.  Asynchronous on the stream.
+    """
+    if Q.dtype == torch.bfloat16:
+        dt = AP_BF16
+    elif Q.dtype == torch.float32:
+        dt = AP_F32
+    else:
+        raise ValueError("dtype must be float32 or bfloat16")
+    if K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise ValueError("Q, K, V must share a dtype")
+    if Q.dim() != 4 or K.dim() != 4 or V.dim() != 4:
+        raise ValueError("Q, K, V must be [B, H, L, D]")
+    B, H, Lq, D = Q.shape
+    Lk = K.shape[2]
+    if tuple(K.shape) != (B, H, Lk, D) or tuple(V.shape) != (B, H, Lk, D):
+        raise ValueError("K/V shape mismatch")
+    if (H, Lq, Lk) != (layout.H, layout.Lq, layout.Lk):
+        raise ValueError("layout was built for other sizes")
+    for t in (Q, K, V):
+        if t.stride(3) != 1:
+            raise ValueError("last dimension must be contiguous")
+    if out is None:
+        out = torch.empty((B, H, Lq, D), dtype=Q.dtype, device=Q.device)
+    if lse is None and return_lse:
+        lse = torch.empty((B, H, Lq), dtype=torch.float32, device=Q.device)
+    st = lib().ap_sparse_attn_fwd(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+        lse.data_ptr() if lse is not None else None, dt, B, H, Lq, Lk, D,
+        _strides3(Q), _strides3(K), _strides3(V), _strides3(out),
+        layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
+        layout.block_m, layout.block_n, int(bool(causal)), float(softmax_scale),
+        _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_sparse_attn_fwd")
+    return out, lse

@@ -1,0 +1,122 @@
+// C ABI of the library: host-side validation and dispatch.  See include/ap.h for the contract.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "ap.h"
+#include "ap_internal.h"
+
+namespace {
+
+inline bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+bool strides_ok(const int64_t* s, int D, int elems_per_16b)
+{
+    for (int k = 0; k < 3; ++k)
+        if (s[k] < 0 || s[k] % elems_per_16b != 0) return false;
+    return s[2] >= D;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ap_status_string(ap_status s)
+{
+    switch (s) {
+    case AP_OK: return "AP_OK";
+    case AP_ERR_INVALID_ARG: return "AP_ERR_INVALID_ARG";
+    case AP_ERR_UNSUPPORTED: return "AP_ERR_UNSUPPORTED";
+    case AP_ERR_CAPACITY: return "AP_ERR_CAPACITY";
+    case AP_ERR_HIP: return "AP_ERR_HIP";
+    }
+    return "AP_ERR_UNKNOWN";
+}
+
+int64_t ap_layout_max_tiles(int H, int Lq, int Lk, int block_m, int block_n)
+{
+    if (!ap::layout_shape_ok(H, Lq, Lk, block_m, block_n)) return -1;
+    const int64_t nQB = (Lq + block_m - 1) / block_m, nKB = (Lk + block_n - 1) / block_n;
+    return (int64_t)H * nQB * nKB;
+}
+
+size_t ap_layout_workspace_bytes(int H, int Lq, int Lk, int block_m, int block_n)
+{
+    if (!ap::layout_shape_ok(H, Lq, Lk, block_m, block_n)) return 0;
+    size_t f, c, d, total;
+    ap::layout_workspace_plan(H, Lq, Lk, block_m, block_n, &f, &c, &d, &total);
+    return total;
+}
+
+ap_status ap_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int block_m, int block_n,
+                          int32_t* row_ptr, int32_t* col_idx, uint64_t* bitmaps, int64_t cap,
+                          int64_t* nnz_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (H <= 0 || Lq <= 0 || Lk <= 0 || block_m <= 0 || block_n <= 0) return AP_ERR_INVALID_ARG;
+    if (!ap::layout_shape_ok(H, Lq, Lk, block_m, block_n)) return AP_ERR_UNSUPPORTED;
+    if (!mask || !row_ptr || !workspace) return AP_ERR_INVALID_ARG;
+    if ((col_idx == nullptr) != (bitmaps == nullptr)) return AP_ERR_INVALID_ARG;
+    if (col_idx && cap < 0) return AP_ERR_INVALID_ARG;
+    if (!aligned(row_ptr, 4) || !aligned(col_idx, 4) || !aligned(bitmaps, 8) ||
+        !aligned(nnz_out, 8) || !aligned(workspace, 8))
+        return AP_ERR_INVALID_ARG;
+    if (workspace_bytes < ap_layout_workspace_bytes(H, Lq, Lk, block_m, block_n)) return AP_ERR_CAPACITY;
+
+    const hipError_t e = ap::launch_build_layout(mask, H, Lq, Lk, block_m, block_n, row_ptr, col_idx,
+                                                 bitmaps, (long long)cap, nnz_out, workspace,
+                                                 (hipStream_t)stream);
+    return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* lse,
+                             ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                             const int64_t* stride_q, const int64_t* stride_k,
+                             const int64_t* stride_v, const int64_t* stride_o,
+                             const int32_t* row_ptr, const int32_t* col_idx,
+                             const uint64_t* bitmaps, int block_m, int block_n, int causal,
+                             float softmax_scale, void* stream)
+{
+    if (!Q || !K || !V || !O || !stride_q || !stride_k || !stride_v || !stride_o || !row_ptr ||
+        !col_idx || !bitmaps)
+        return AP_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || Lq <= 0 || Lk <= 0 || D <= 0 || block_m <= 0 || block_n <= 0)
+        return AP_ERR_INVALID_ARG;
+    if (dtype != AP_F32 && dtype != AP_BF16) return AP_ERR_INVALID_ARG;
+    if (causal && Lk < Lq) return AP_ERR_INVALID_ARG;
+    if (O == Q || O == K || O == V) return AP_ERR_INVALID_ARG;
+    if (isnan(softmax_scale) || isinf(softmax_scale)) return AP_ERR_INVALID_ARG;
+
+    if (!(D == 32 || D == 64 || D == 128)) return AP_ERR_UNSUPPORTED;
+    if (block_n != 64) return AP_ERR_UNSUPPORTED;
+    if (!(block_m == 64 || (block_m == 128 && dtype == AP_BF16))) return AP_ERR_UNSUPPORTED;
+    const long long nQB = (Lq + block_m - 1) / block_m;
+    if (nQB * H * B >= 2147483647LL || H > 65535 || B > 65535) return AP_ERR_UNSUPPORTED;
+
+    const int per16 = dtype == AP_BF16 ? 8 : 4;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) ||
+        !aligned(lse, 4) || !aligned(row_ptr, 4) || !aligned(col_idx, 4) || !aligned(bitmaps, 8))
+        return AP_ERR_INVALID_ARG;
+    if (!strides_ok(stride_q, D, per16) || !strides_ok(stride_k, D, per16) ||
+        !strides_ok(stride_v, D, per16) || !strides_ok(stride_o, D, per16))
+        return AP_ERR_INVALID_ARG;
+
+    ap::FwdArgs a;
+    a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
+    a.B = B; a.H = H; a.Lq = Lq; a.Lk = Lk; a.D = D;
+    for (int k = 0; k < 3; ++k) {
+        a.sq[k] = stride_q[k]; a.sk[k] = stride_k[k]; a.sv[k] = stride_v[k]; a.so[k] = stride_o[k];
+    }
+    a.row_ptr = row_ptr; a.col_idx = col_idx; a.bitmaps = bitmaps;
+    a.block_m = block_m; a.block_n = block_n;
+    a.causal = causal ? 1 : 0;
+    a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+
+    hipError_t e;
+    if (dtype == AP_BF16)
+        e = ap::launch_fwd_mfma(a, (hipStream_t)stream);
+    else
+        e = ap::launch_fwd_valu(a, false, (hipStream_t)stream);
+    return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+}  // extern "C"

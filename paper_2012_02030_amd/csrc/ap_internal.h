@@ -1,0 +1,40 @@
+// Declarations shared by the library's own translation units (never by the test oracle).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ap {
+
+// ---- layout pass (ap_layout.hip)
+bool layout_shape_ok(int H, int Lq, int Lk, int BM, int BN);
+void layout_workspace_plan(int H, int Lq, int Lk, int BM, int BN, size_t* flags_off,
+                           size_t* counts_off, size_t* dense_off, size_t* total);
+hipError_t launch_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int BM, int BN,
+                               int32_t* row_ptr, int32_t* col_idx, uint64_t* bitmaps,
+                               long long cap, int64_t* nnz_out, void* workspace,
+                               hipStream_t stream);
+
+// ---- attention forward (ap_attn_valu.hip, ap_attn_mfma.hip)
+struct FwdArgs {
+    const void* Q;
+    const void* K;
+    const void* V;
+    void* O;
+    float* lse;                     // may be null
+    int B, H, Lq, Lk, D;
+    long long sq[3], sk[3], sv[3], so[3];   // element strides: batch, head, sequence
+    const int32_t* row_ptr;
+    const int32_t* col_idx;
+    const uint64_t* bitmaps;
+    int block_m, block_n;
+    int causal;
+    float scale;                    // already resolved (> 0)
+};
+
+// fp32-arithmetic kernel (one query per lane); handles fp32 and bf16 storage, block 64x64
+hipError_t launch_fwd_valu(const FwdArgs& a, bool bf16, hipStream_t stream);
+// bf16 matrix-core kernel; block_m 64 or 128, block_n 64
+hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream);
+
+}  // namespace ap

@@ -115,11 +115,24 @@ def head_mask(cfg: Config, h: int) -> np.ndarray:
     return keep
 
 
-def make_mask(cfg: Config) -> np.ndarray:
-    """uint8 keep-mask [H, Lq, Lk] (1 = kept) for all heads of cfg."""
+def make_mask(cfg: Config, workers: int = 8) -> np.ndarray:
+    """uint8 keep-mask [H, Lq, Lk] (1 = kept) for all heads of cfg.
+
+    Heads are independent (each has its own seed), so they are drawn on a small thread pool;
+    the result does not depend on the number of workers.
+    """
     out = np.empty((cfg.H, cfg.Lq, cfg.Lk), dtype=np.uint8)
-    for h in range(cfg.H):
+
+    def one(h):
         out[h] = head_mask(cfg, h)
+
+    if cfg.Lq * cfg.Lk < (1 << 20) or workers <= 1:
+        for h in range(cfg.H):
+            one(h)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(workers, cfg.H)) as pool:
+            list(pool.map(one, range(cfg.H)))
     return out
 
 

@@ -1,0 +1,106 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes its buffers as documented and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2012_02030_amd import binding as ap
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(ap.LIB_PATH):
+        from paper_2012_02030_amd import build
+        build.build()
+    return ap.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ap_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert set(ap.SYMBOLS) == set(names)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings(L):
+    assert ap.ap_status_string(0) == "AP_OK"
+    assert ap.ap_status_string(-1) == "AP_ERR_INVALID_ARG"
+    assert ap.ap_status_string(-2) == "AP_ERR_UNSUPPORTED"
+    assert ap.ap_status_string(-3) == "AP_ERR_CAPACITY"
+    assert ap.ap_status_string(-4) == "AP_ERR_HIP"
+
+
+def test_layout_sizes(L):
+    assert ap.ap_layout_max_tiles(16, 4096, 4096, 64, 64) == 16 * 64 * 64
+    assert ap.ap_layout_max_tiles(2, 65, 130, 64, 64) == 2 * 2 * 3
+    assert ap.ap_layout_max_tiles(1, 64, 64, 48, 64) == -1          # unsupported block size
+    assert ap.ap_layout_max_tiles(0, 64, 64, 64, 64) == -1
+    ws = ap.ap_layout_workspace_bytes(16, 4096, 4096, 64, 64)
+    tiles = 16 * 64 * 64
+    assert ws >= tiles * 64 * 8 + tiles + 16 * 64 * 4                # dense bitmaps + flags + counts
+    assert ws < 1.1 * (tiles * 64 * 8 + tiles + 16 * 64 * 4) + 64
+    assert ap.ap_layout_workspace_bytes(1, 64, 64, 48, 64) == 0
+
+
+def test_build_layout_rejects_bad_arguments(L):
+    fake = 0x1000   # never dereferenced: validation fails first
+    call = L.ap_build_layout
+    ok_ws = ap.ap_layout_workspace_bytes(2, 64, 64, 64, 64)
+    assert call(None, 2, 64, 64, 64, 64, fake, fake, fake, 8, fake, fake, ok_ws, None) == ap.AP_ERR_INVALID_ARG
+    assert call(fake, 0, 64, 64, 64, 64, fake, fake, fake, 8, fake, fake, ok_ws, None) == ap.AP_ERR_INVALID_ARG
+    assert call(fake, 2, 64, 64, 48, 64, fake, fake, fake, 8, fake, fake, ok_ws, None) == ap.AP_ERR_UNSUPPORTED
+    assert call(fake, 2, 64, 64, 64, 64, fake, fake, None, 8, fake, fake, ok_ws, None) == ap.AP_ERR_INVALID_ARG
+    assert call(fake, 2, 64, 64, 64, 64, fake, fake, fake, -1, fake, fake, ok_ws, None) == ap.AP_ERR_INVALID_ARG
+    assert call(fake, 2, 64, 64, 64, 64, fake, fake, fake + 4, 8, fake, fake, ok_ws, None) == ap.AP_ERR_INVALID_ARG
+    assert call(fake, 2, 64, 64, 64, 64, fake, fake, fake, 8, fake, fake, ok_ws - 1, None) == ap.AP_ERR_CAPACITY
+    assert call(fake, 2, 64, 64, 64, 64, fake, fake, fake, 8, fake, None, ok_ws, None) == ap.AP_ERR_INVALID_ARG
+
+
+def _fwd(L, **over):
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+    a = dict(Q=fake, K=fake + 0x100000, V=fake + 0x200000, O=fake + 0x300000, lse=None, dtype=ap.AP_BF16,
+             B=1, H=2, Lq=64, Lk=64, D=64, sq=s, sk=s, sv=s, so=s, row_ptr=fake, col_idx=fake,
+             bitmaps=fake, bm=64, bn=64, causal=0, scale=0.0)
+    a.update(over)
+    return L.ap_sparse_attn_fwd(a["Q"], a["K"], a["V"], a["O"], a["lse"], a["dtype"], a["B"], a["H"],
+                                a["Lq"], a["Lk"], a["D"], a["sq"], a["sk"], a["sv"], a["so"],
+                                a["row_ptr"], a["col_idx"], a["bitmaps"], a["bm"], a["bn"],
+                                a["causal"], a["scale"], None)
+
+
+def test_fwd_rejects_bad_arguments(L):
+    assert _fwd(L, Q=None) == ap.AP_ERR_INVALID_ARG
+    assert _fwd(L, bitmaps=None) == ap.AP_ERR_INVALID_ARG
+    assert _fwd(L, B=0) == ap.AP_ERR_INVALID_ARG
+    assert _fwd(L, dtype=7) == ap.AP_ERR_INVALID_ARG
+    assert _fwd(L, D=48) == ap.AP_ERR_UNSUPPORTED
+    assert _fwd(L, D=256) == ap.AP_ERR_UNSUPPORTED
+    assert _fwd(L, bn=32) == ap.AP_ERR_UNSUPPORTED
+    assert _fwd(L, bm=32) == ap.AP_ERR_UNSUPPORTED
+    assert _fwd(L, bm=128, dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    assert _fwd(L, causal=1, Lq=128, Lk=64) == ap.AP_ERR_INVALID_ARG          # Lk < Lq with causal
+    assert _fwd(L, Q=0x1008) == ap.AP_ERR_INVALID_ARG                          # not 16-byte aligned
+    assert _fwd(L, O=0x1000) == ap.AP_ERR_INVALID_ARG                          # O aliases Q
+    bad = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 60)
+    assert _fwd(L, sk=bad) == ap.AP_ERR_INVALID_ARG                            # row stride not 16-byte multiple
+    short = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 32)
+    assert _fwd(L, sv=short) == ap.AP_ERR_INVALID_ARG                          # row stride < D
+    assert _fwd(L, scale=float("nan")) == ap.AP_ERR_INVALID_ARG
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(ap, "_lib", None)
+    monkeypatch.setattr(ap, "LIB_PATH", "/nonexistent/libap_mi355x.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        ap.lib()
