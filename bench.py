@@ -1,0 +1,289 @@
+#!/usr/bin/env python3
+"""Benchmark of the masked-attention forward path on one MI355X.
+
+A step is one call of ap_sparse_attn_fwd over one batch of synthetic input with the tensors
+already resident in HBM.  The layout is built once before the timed region: the mask of
+Attention Pruning is fixed for all inputs (Section 3.2), so ap_build_layout runs once per
+layer and is amortised over every forward call; its own time is reported as `layout_ms`.
+
+Prints ONE JSON line.  `value` is kept-entry TFLOP/s (4*D flops per kept connection per batch
+element) of the headline workload; `per_config` carries ms/call, roofline fraction and the
+speedup over the same kernel run with a dense mask for every configuration.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
+INFINITY_CACHE_BYTES = 256 << 20
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=200)
+    p.add_argument("--warmup", type=int, default=20)
+    p.add_argument("--workload", default="C5", help="headline configuration (C1..C5)")
+    p.add_argument("--block-m", type=int, default=64)
+    p.add_argument("--only", action="store_true", help="skip the per-config table and the CPU baseline")
+    p.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over batch and heads with "
+              "no exchange; no multi-GPU figure is produced). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2012_02030_amd import binding as ap
+    from paper_2012_02030_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    ap.lib()                                            # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+
+    def log(*a):
+        print(*a, file=sys.stderr, flush=True)
+
+    def alg_bytes(cfg):
+        es = 4 if cfg.dtype == "f32" else 2
+        return es * cfg.B * cfg.H * cfg.D * (2 * cfg.Lq + 2 * cfg.Lk)      # Q, O and K, V once each
+
+    def tensor_sets(cfg, n_sets):
+        """Set 0 is the seeded numpy draw the tests use; further sets are seeded device draws."""
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+        sets = []
+        q, k, v = synth.make_qkv(cfg)
+        sets.append(tuple(torch.from_numpy(x).to(tdt).to(dev) for x in (q, k, v)))
+        gen = torch.Generator(device=dev)
+        for s in range(1, n_sets):
+            gen.manual_seed(synth.SEED + 1000 * cfg.index + s)
+            sets.append(tuple(
+                torch.randn((cfg.B, cfg.H, L, cfg.D), generator=gen, device=dev, dtype=torch.float32).to(tdt)
+                for L in (cfg.Lq, cfg.Lk, cfg.Lk)))
+        outs = [torch.empty_like(s[0]) for s in sets]
+        lses = [torch.empty((cfg.B, cfg.H, cfg.Lq), dtype=torch.float32, device=dev) for _ in sets]
+        return sets, outs, lses
+
+    def n_sets_for(cfg):
+        # rotate through enough independent sets that no call finds its inputs in the 256 MB cache
+        return max(2, -(-2 * INFINITY_CACHE_BYTES // alg_bytes(cfg)) + 1)
+
+    def time_calls(cfg, layout, sets, outs, lses, steps, warmup):
+        """Exactly `steps` back-to-back launches on the current stream, one HIP event between
+        each pair; returns (wall ms per step, list of per-launch ms)."""
+        n = len(sets)
+
+        def call(i):
+            q, k, v = sets[i % n]
+            ap.ap_sparse_attn_fwd(q, k, v, layout, causal=cfg.causal, out=outs[i % n], lse=lses[i % n])
+
+        for i in range(warmup):
+            call(i)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        evs[0].record()
+        for i in range(steps):
+            call(i)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        per = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+        return wall_ms, per
+
+    def time_graph(cfg, layout, sets, outs, lses, steps, warmup):
+        """For microsecond-scale kernels the Python launch rate, not the GPU, would set the pace:
+        capture one rotation through all sets into a HIP graph and time its replays."""
+        n = len(sets)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(n):
+                q, k, v = sets[i]
+                ap.ap_sparse_attn_fwd(q, k, v, layout, causal=cfg.causal, out=outs[i], lse=lses[i])
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(n):
+                q, k, v = sets[i]
+                ap.ap_sparse_attn_fwd(q, k, v, layout, causal=cfg.causal, out=outs[i], lse=lses[i])
+        reps = max(1, -(-steps // n))
+        for _ in range(max(1, warmup // n)):
+            g.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * n)
+
+    def run_config(cfg, mask_np, steps, warmup, block_m, use_graph):
+        """AP-mask run and dense-mask run of the same kernel; returns a result dict."""
+        dmask = torch.from_numpy(mask_np).to(dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ap.ap_build_layout(dmask, block_m, 64)                       # warm-up of the layout kernels
+        torch.cuda.synchronize()
+        e0.record()
+        layout = ap.ap_build_layout(dmask, block_m, 64)
+        e1.record()
+        torch.cuda.synchronize()
+        layout_ms = e0.elapsed_time(e1)
+        dense_layout = ap.ap_build_layout(torch.ones_like(dmask), block_m, 64)
+        torch.cuda.synchronize()
+        del dmask
+
+        sets, outs, lses = tensor_sets(cfg, n_sets_for(cfg))
+        wall_ms, per = time_calls(cfg, layout, sets, outs, lses, steps, warmup)
+        dsteps = max(10, steps // 4)
+        dwall_ms, dper = time_calls(cfg, dense_layout, sets, outs, lses, dsteps, max(2, warmup // 4))
+        ms = float(np.mean(per))
+        dms = float(np.mean(dper))
+        gms = gdms = None
+        if use_graph:
+            try:
+                gms = time_graph(cfg, layout, sets, outs, lses, steps, warmup)
+                gdms = time_graph(cfg, dense_layout, sets, outs, lses, dsteps, warmup)
+            except Exception as ex:                                   # graph capture is an extra
+                log("graph timing unavailable:", repr(ex))
+        kernel_ms = gms if gms is not None else ms
+        dense_kernel_ms = gdms if gdms is not None else dms
+
+        kept = int(mask_np.sum())                                     # causal already folded in by the generator
+        kept_flop = 4.0 * cfg.D * kept * cfg.B
+        if cfg.causal:
+            dense_entries = cfg.H * sum(min(cfg.Lk, i + 1 + cfg.Lk - cfg.Lq) for i in range(cfg.Lq))
+        else:
+            dense_entries = cfg.H * cfg.Lq * cfg.Lk
+        dense_flop = 4.0 * cfg.D * dense_entries * cfg.B
+        nnz = int(layout.nnz.item())
+        tile_flop = 4.0 * cfg.D * block_m * 64 * nnz * cfg.B           # matrix-core work of the visited tiles
+        res = {
+            "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D,
+                      "dtype": cfg.dtype, "causal": cfg.causal},
+            "kept_entries_per_batch": kept,
+            "keep_density": kept / float(dense_entries),
+            "tiles_stored": nnz,
+            "tiles_max": int(ap.ap_layout_max_tiles(cfg.H, cfg.Lq, cfg.Lk, block_m, 64)),
+            "ms_per_call": kernel_ms,
+            "ms_per_call_stream_launches": ms,
+            "ms_per_call_median": float(np.median(per)),
+            "ms_per_call_min": float(np.min(per)),
+            "wall_ms_per_step": wall_ms,
+            "kept_tflops": kept_flop / (kernel_ms * 1e-3) / 1e12,
+            "hbm_alg_bytes": alg_bytes(cfg),
+            "hbm_gbs": alg_bytes(cfg) / (kernel_ms * 1e-3) / 1e9,
+            "hbm_roofline_frac": alg_bytes(cfg) / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "tile_mfma_tflops": tile_flop / (kernel_ms * 1e-3) / 1e12,
+            "dense_ms_per_call": dense_kernel_ms,
+            "dense_tflops": dense_flop / (dense_kernel_ms * 1e-3) / 1e12,
+            "dense_mfma_frac": dense_flop / (dense_kernel_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "speedup_vs_dense": dense_kernel_ms / kernel_ms,
+            "layout_ms": layout_ms,
+            "layout_gbs": mask_np.size / (layout_ms * 1e-3) / 1e9,
+            "timing": "hip graph replay" if gms is not None else "stream launches",
+            "n_buffer_sets": len(sets),
+        }
+        keep_for_parity = (sets[0], outs, lses, layout)
+        return res, keep_for_parity
+
+    # ---------------------------------------------------------------- headline workload
+    head = synth.CONFIGS[args.workload]
+    log("generating", head.name, "mask ...")
+    head_mask = synth.make_mask(head)
+    small = head.name != "C5"
+    log("timing", head.name, "...")
+    head_res, (set0, outs, lses, layout) = run_config(head, head_mask, args.steps, args.warmup,
+                                                     args.block_m, use_graph=small)
+
+    # ---------------------------------------------------------------- CPU baseline = the oracle
+    cpu = None
+    parity = None
+    if not args.only and not args.no_cpu:
+        import oracle
+        q, k, v = set0
+        ap.ap_sparse_attn_fwd(q, k, v, layout, causal=head.causal, out=outs[0], lse=lses[0])
+        torch.cuda.synchronize()
+        rq, rk, rv = (x.to(torch.float64).cpu().numpy() for x in (q, k, v))
+        log("timing the CPU oracle on the full", head.name, "workload ...")
+        t0 = time.perf_counter()
+        O_ref, lse_ref = oracle.masked_attention(rq, rk, rv, head_mask, causal=head.causal)
+        cpu_s = time.perf_counter() - t0
+        kept_flop = 4.0 * head.D * int(head_mask.sum()) * head.B
+        cpu = {"value": kept_flop / cpu_s / 1e12, "unit": "TFLOP/s (kept-entry)", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": "full %s workload, one call, fp64" % head.name,
+               "ms_per_call": cpu_s * 1e3}
+        parity = {"max_abs_err_O": float(np.abs(outs[0].to(torch.float64).cpu().numpy() - O_ref).max()),
+                  "max_abs_err_lse": float(np.abs(lses[0].to(torch.float64).cpu().numpy() - lse_ref).max()),
+                  "tolerance": 2e-2 if head.dtype == "bf16" else 1e-5}
+        del rq, rk, rv, O_ref, lse_ref
+    del set0, outs, lses, layout
+    torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- the other configurations
+    per_config = {head.name: head_res}
+    if not args.only:
+        for name, cfg in synth.CONFIGS.items():
+            if name == head.name:
+                continue
+            log("timing", name, "...")
+            steps = min(args.steps, 200)
+            res, keep = run_config(cfg, synth.make_mask(cfg), steps, args.warmup, args.block_m,
+                                   use_graph=(name != "C5"))
+            del keep
+            torch.cuda.empty_cache()
+            per_config[name] = res
+
+    out = {
+        "metric": "kept-entry TFLOP/s of masked attention fwd (ms/call and speedup vs dense-mask run alongside)",
+        "value": head_res["kept_tflops"],
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head_res["wall_ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": head.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s: B%d H%d Lq%d Lk%d D%d %s %s, keep %.0f%% of %s entries per head" % (
+            head.name, head.B, head.H, head.Lq, head.Lk, head.D, head.dtype,
+            "causal" if head.causal else "non-causal", 100 * head.keep,
+            "causal" if head.causal else "all"),
+            "block_m": args.block_m, "block_n": 64},
+        "ms_per_call": head_res["ms_per_call"],
+        "speedup_vs_dense": head_res["speedup_vs_dense"],
+        "layout_ms": head_res["layout_ms"],
+        "roofline": {"bound": "hbm", "achieved": head_res["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": head_res["hbm_roofline_frac"], "traffic": None,
+                     "kernel": "fwd_mfma_kernel" if head.dtype == "bf16" else "fwd_valu_kernel",
+                     "algorithmic_bytes_per_launch": head_res["hbm_alg_bytes"]},
+        "roofline_dense_run": {"bound": "mfma", "achieved": head_res["dense_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
+                               "unit": "TFLOP/s", "frac": head_res["dense_mfma_frac"]},
+        "cpu_baseline": cpu,
+        "parity": parity,
+        "per_config": per_config,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

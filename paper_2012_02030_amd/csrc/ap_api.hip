@@ -100,6 +100,11 @@ ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* 
         !strides_ok(stride_v, D, per16) || !strides_ok(stride_o, D, per16))
         return AP_ERR_INVALID_ARG;
 
+    // the matrix-core kernel addresses each (batch, head) slice of K and V with 32-bit byte offsets
+    if (dtype == AP_BF16 && ((long long)Lk * stride_k[2] * 2 >= 2147483647LL ||
+                             (long long)Lk * stride_v[2] * 2 >= 2147483647LL))
+        return AP_ERR_UNSUPPORTED;
+
     ap::FwdArgs a;
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
     a.B = B; a.H = H; a.Lq = Lq; a.Lk = Lk; a.D = D;

@@ -2,17 +2,22 @@
 //
 // One workgroup per block row of the layout (block_m = 32 * NW queries, one wavefront per 32
 // queries).  The workgroup walks only the stored tiles of its block row.  Per tile:
-//   1. the 64 key rows and 64 value rows are staged in LDS with coalesced 128-bit loads;
+//   1. the 64 key rows and 64 value rows go from HBM/L2 straight into LDS with 128-bit
+//      buffer loads that write LDS directly (no staging registers); the next tile's loads are
+//      issued before the current tile is computed (two LDS stages) so they fly under the math;
+//      LDS rows are unpadded and XOR-swizzled in 16-byte chunks so that both the key-operand
+//      reads and the transposing value reads are bank-conflict free;
 //   2. S^T = K Q^T on v_mfma_f32_32x32x16_bf16, so that every lane holds scores of ONE query
 //      (lane % 32) for 32 of the 64 keys -- the row maximum is an in-register reduction plus
 //      a single exchange with lane ^ 32, and the row sum needs no exchange until the end;
 //   3. the lane's 64-bit bitmap word (and the causal limit) turns pruned scores into -inf in
-//      registers, before the exponential;
+//      registers, before the exponential; tiles whose visible part is all ones skip this;
 //   4. online softmax in fp32 (exp2 with scale*log2(e) folded into one fma);
 //   5. O^T += V^T P^T on the matrix cores: the S^T accumulator registers already have the
 //      lane layout of the P^T operand, and V^T is read from the row-major LDS tile with the
 //      transposing LDS read, so nothing is shuffled.
-// O is normalised and written once at the end together with the optional log-sum-exp.
+// O is normalised, staged through LDS and written with coalesced 128-bit stores, together with
+// the optional log-sum-exp.
 //
 // Matrix-core register layouts used below (32x32x16, 64 lanes, l = lane):
 //   A[m][k]: m = l % 32, k = 8*(l/32) + e, e = 0..7        B[k][n]: n = l % 32, same k
@@ -20,8 +25,14 @@
 // The contraction index of the second product runs over keys in the order the S^T registers
 // hold them (slot (l/32, e) of 16-key step ks is key 16*ks + 8*(e/4) + 4*(l/32) + e%4); both
 // operands use the same order, which leaves the sum unchanged.
+//
+// The transposing LDS read (ds_read_b64_tr_b16) works on groups of 16 lanes: lane i of a group
+// supplies the address of 4 consecutive 16-bit elements, and receives element (i % 4) of the
+// data addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12.  With lanes 4j..4j+3 pointing at 16
+// consecutive columns of row j, lane i ends up with column i of rows 0..3.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "ap_internal.h"
 
@@ -33,16 +44,21 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
 
 constexpr int kBN = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-template <int D>
-struct Tile {
-    static constexpr int KSTR = D + 8;                       // bf16 elements per LDS key row
-    static constexpr int VSTR = (D == 32) ? 96 : D + 32;     // bf16 elements per LDS value row
-};
+// Swizzles: the 16-byte chunk c of LDS row r is stored at chunk position c ^ f(r).
+// Key rows are read as one chunk per lane by 32 consecutive rows; value rows are read by the
+// transposing load, 8 rows x 64 bytes per wavefront instruction.
+template <int D> __device__ __forceinline__ int swz_k(int r) { return (r * (D / 8) / 16) % (D / 8); }
+template <int D> __device__ __forceinline__ int swz_v(int r)
+{
+    return D == 128 ? 4 * (r & 3) : (D == 64 ? 4 * ((r >> 1) & 1) : 0);
+}
 
 __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
 {
@@ -52,21 +68,45 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
     return (a >> 16) | (b & 0xffff0000u);
 }
 
-template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(FwdArgs a, int nQB)
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Issue the loads of one 64-row tile (rows row0.. of a [rows, D] bf16 slice described by the
+// buffer resource) into LDS.  Every wavefront instruction moves 64 x 16 bytes = 1 KB.
+template <int D, int NW, bool IS_V>
+__device__ __forceinline__ void issue_tile_loads(__amdgpu_buffer_rsrc_t rsrc, lds_u16* dst,
+                                                 int row0, int stride_bytes, int wave, int lane)
+{
+    constexpr int CPR = D / 8;                // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;             // rows per wavefront instruction
+    constexpr int NI = kBN / RPI;             // instructions per tile
+    static_assert(NI % NW == 0 || NI < NW, "instructions must divide over the wavefronts");
+    const int rl = lane / CPR;                // row inside the instruction
+    const int cp = lane % CPR;                // chunk position in LDS
+#pragma unroll
+    for (int u = 0; u < (NI + NW - 1) / NW; ++u) {
+        const int j = wave + NW * u;
+        if (NI < NW && j >= NI) break;        // wave-uniform
+        const int r = j * RPI + rl;           // row inside the tile
+        const int c = cp ^ (IS_V ? swz_v<D>(r) : swz_k<D>(r));
+        const int voff = rl * stride_bytes + c * 16;
+        const int soff = (row0 + j * RPI) * stride_bytes;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(dst + j * 512), 16, voff, soff, 0, 0);
+    }
+}
+
+template <int D, int NW, int STAGES>
+__global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB, int xcd_chunk)
 {
     constexpr int BM = 32 * NW;
-    constexpr int NT = 64 * NW;
-    constexpr int KSTR = Tile<D>::KSTR;
-    constexpr int VSTR = Tile<D>::VSTR;
     constexpr int KSTEPS = D / 16;                           // contraction steps of Q K^T
     constexpr int DBLK = D / 32;                             // 32-wide blocks of the head dim
     constexpr int CPR = D / 8;                               // 16-byte chunks per row
-    constexpr int CHUNKS = (kBN * CPR) / NT;                 // chunks per thread per operand
-    static_assert((kBN * CPR) % NT == 0, "tile must divide evenly over the threads");
+    constexpr int TILE = kBN * D;                            // elements of one K or V tile
+    constexpr int OSTAGE = BM * D;                           // elements needed to stage O
+    constexpr int SMEM = (STAGES * 2 * TILE > OSTAGE) ? STAGES * 2 * TILE : OSTAGE;
 
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[kBN * KSTR];
-    __shared__ __attribute__((aligned(16))) uint16_t Vs[kBN * VSTR];
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[SMEM];
+    lds_u16* lds = (lds_u16*)smem;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -74,9 +114,11 @@ __global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(FwdArgs a, int nQB)
     const int n = lane & 31;                                 // query inside the wavefront's 32
     const int hh = lane >> 5;                                // which half of the key slots
 
-    // block row: long causal rows are issued first
-    const int bid = blockIdx.x;
-    const int qb = nQB - 1 - (bid % nQB);
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
+    // (batch, head) pairs so that the block rows sharing K and V also share an L2.
+    int bid = blockIdx.x;
+    if (xcd_chunk > 0) bid = (bid & 7) * xcd_chunk + (bid >> 3);
+    const int qb = nQB - 1 - (bid % nQB);                    // long causal rows first
     const int h = (bid / nQB) % a.H;
     const int b = bid / (nQB * a.H);
 
@@ -84,6 +126,12 @@ __global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(FwdArgs a, int nQB)
     const uint16_t* Kp = (const uint16_t*)a.K + (size_t)b * a.sk[0] + (size_t)h * a.sk[1];
     const uint16_t* Vp = (const uint16_t*)a.V + (size_t)b * a.sv[0] + (size_t)h * a.sv[1];
     uint16_t* Op = (uint16_t*)a.O + (size_t)b * a.so[0] + (size_t)h * a.so[1];
+    const int sk_bytes = (int)a.sk[2] * 2, sv_bytes = (int)a.sv[2] * 2;
+    // rows >= Lk lie beyond num_records: the hardware returns zeros for them
+    const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)Kp, 0, (a.Lk - 1) * sk_bytes + D * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)Vp, 0, (a.Lk - 1) * sv_bytes + D * 2, 0x00020000);
 
     const int brow = wave * 32 + n;                          // row inside the block row
     const int qrow = qb * BM + brow;                         // this lane's query
@@ -108,148 +156,193 @@ __global__ __launch_bounds__(64 * NW) void fwd_mfma_kernel(FwdArgs a, int nQB)
     const float sc = a.scale * kLog2e;
 
     const int r = h * nQB + qb;
-    const int t_begin = a.row_ptr[r], t_end = a.row_ptr[r + 1];
+    const int t_begin = a.row_ptr[r];
+    int nt = a.row_ptr[r + 1] - t_begin;
     const long long off = (long long)a.Lk - a.Lq;
     const long long diag = (long long)qrow + off;            // last visible key if causal
-    const long long block_diag = (long long)qb * BM + (BM - 1) + off;
+    if (a.causal) {                                          // drop tiles that are entirely in the future
+        const long long block_diag = (long long)qb * BM + (BM - 1) + off;
+        while (nt > 0 && (long long)a.col_idx[t_begin + nt - 1] * kBN > block_diag) --nt;
+    }
 
-    for (int t = t_begin; t < t_end; ++t) {
-        const int k0 = a.col_idx[t] * kBN;
-        if (a.causal && (long long)k0 > block_diag) break;   // this and all later tiles are hidden
+    // per-lane LDS read offsets (elements), loop invariant
+    const int k_swz = (hh ^ swz_k<D>(n));                    // rows n and n + 32 share the swizzle
+    const int i16 = lane & 15, g = (lane >> 4) & 1, vj = i16 >> 2;
+    const int v_lane_row = 4 * hh + vj;
+    const int v_in_chunk = 4 * (i16 & 1);
+    const int v_chunk_lo = 2 * g + ((i16 >> 1) & 1);
+    const int v_swz = swz_v<D>(vj) >> 2;                     // xor on the 4-chunk group index
 
-        uint64_t word = a.bitmaps[(size_t)t * BM + brow];
+    // first tile
+    uint64_t word_next = 0;
+    int k0_next = 0;
+    if (nt > 0) {
+        k0_next = a.col_idx[t_begin] * kBN;
+        issue_tile_loads<D, NW, false>(k_rsrc, lds, k0_next, sk_bytes, wave, lane);
+        issue_tile_loads<D, NW, true>(v_rsrc, lds + TILE, k0_next, sv_bytes, wave, lane);
+        word_next = a.bitmaps[(size_t)t_begin * BM + brow];
+    }
+
+    for (int it = 0; it < nt; ++it) {
+        const int stage = (STAGES == 2) ? (it & 1) : 0;
+        lds_u16* Ks = lds + stage * 2 * TILE;
+        lds_u16* Vs = Ks + TILE;
+        uint64_t word = word_next;
+        const int k0 = k0_next;
+
+        wait_vmem();                                         // my loads of this tile have landed
+        __syncthreads();                                     // ... and everybody else's
+        if (STAGES == 2 && it + 1 < nt) {
+            const int t1 = t_begin + it + 1;
+            k0_next = a.col_idx[t1] * kBN;
+            lds_u16* Kn = lds + (stage ^ 1) * 2 * TILE;
+            issue_tile_loads<D, NW, false>(k_rsrc, Kn, k0_next, sk_bytes, wave, lane);
+            issue_tile_loads<D, NW, true>(v_rsrc, Kn + TILE, k0_next, sv_bytes, wave, lane);
+            word_next = a.bitmaps[(size_t)t1 * BM + brow];
+        }
+
         if (a.causal) {
             const long long lim = diag - k0;
             if (lim < 0) word = 0;
             else if (lim < 63) word &= (2ull << lim) - 1ull;
         }
 
-        __syncthreads();                                     // everyone is done with the previous tile
-        {
-            uint4 kbuf[CHUNKS], vbuf[CHUNKS];
+        if (__ballot(word != 0) != 0) {                      // something visible for these 32 queries
+            // ---- S^T = K Q^T : two 32-key blocks
+            f32x16 sacc[2];
 #pragma unroll
-            for (int u = 0; u < CHUNKS; ++u) {
-                const int c = tid + u * NT;
-                const int rr = c / CPR, e0 = (c % CPR) * 8;
-                int row = k0 + rr;
-                row = row < a.Lk ? row : a.Lk - 1;
-                kbuf[u] = *reinterpret_cast<const uint4*>(Kp + (size_t)row * a.sk[2] + e0);
-                vbuf[u] = *reinterpret_cast<const uint4*>(Vp + (size_t)row * a.sv[2] + e0);
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const bf16x8 kreg = *reinterpret_cast<const bf16x8*>(
+                        (const uint16_t*)Ks + (kb * 32 + n) * D + ((2 * kk) ^ k_swz) * 8);
+                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg, qreg[kk], sacc[kb], 0, 0, 0);
+                }
             }
+
+            // ---- mask in registers, row maximum
+            float tmax = -INFINITY;
+            if (__ballot(word != ~0ull) == 0) {              // every visible entry kept: no selects
 #pragma unroll
-            for (int u = 0; u < CHUNKS; ++u) {
-                const int c = tid + u * NT;
-                const int rr = c / CPR, e0 = (c % CPR) * 8;
-                *reinterpret_cast<uint4*>(Ks + rr * KSTR + e0) = kbuf[u];
-                *reinterpret_cast<uint4*>(Vs + rr * VSTR + e0) = vbuf[u];
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kb][i]);
+            } else {
+                const uint64_t wsh = word >> (4 * hh);
+                const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int pos = 8 * (i / 4) + (i % 4);
+                        const float s = ((wbits[kb] >> pos) & 1u) ? sacc[kb][i] : -INFINITY;
+                        sacc[kb][i] = s;
+                        tmax = fmaxf(tmax, s);
+                    }
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+
+            // ---- online softmax
+            const float m_new = fmaxf(m, tmax);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f((m - m_use) * sc);
+            const float msc = m_use * sc;
+            m = m_new;
+            float psum = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -msc));
+                    sacc[kb][i] = p;
+                    psum += p;
+                }
+            lsum = lsum * alpha + psum;
+            if (__ballot(alpha != 1.0f) != 0) {
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+            }
+
+            // ---- O^T += V^T P^T
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                bf16x8 pb;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[ks >> 1][8 * (ks & 1) + e];
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db) {
+                    const int chunk = ((db ^ v_swz) << 2) + v_chunk_lo;
+                    lds_u16* p0 = Vs + (16 * ks + v_lane_row) * D + chunk * 8 + v_in_chunk;
+                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p0);
+                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * D));
+                    const bf16x8 vreg = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg, pb, oacc[db], 0, 0, 0);
+                }
             }
         }
-        __syncthreads();
 
-        if (__ballot(word != 0) == 0) continue;              // nothing visible for these 32 queries
-
-        // ---- S^T = K Q^T : two 32-key blocks
-        f32x16 sacc[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const bf16x8 kreg = *reinterpret_cast<const bf16x8*>(
-                    Ks + (kb * 32 + n) * KSTR + 16 * kk + 8 * hh);
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg, qreg[kk], sacc[kb], 0, 0, 0);
-            }
-        }
-
-        // ---- mask in registers, row maximum
-        const uint64_t wsh = word >> (4 * hh);
-        const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
-        float tmax = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int pos = 8 * (i / 4) + (i % 4);
-                const float s = ((wbits[kb] >> pos) & 1u) ? sacc[kb][i] : -INFINITY;
-                sacc[kb][i] = s;
-                tmax = fmaxf(tmax, s);
-            }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-
-        // ---- online softmax
-        const float m_new = fmaxf(m, tmax);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f((m - m_use) * sc);
-        const float msc = m_use * sc;
-        m = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -msc));
-                sacc[kb][i] = p;
-                psum += p;
-            }
-        lsum = lsum * alpha + psum;
-        if (__ballot(alpha != 1.0f) != 0) {
-#pragma unroll
-            for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
-        }
-
-        // ---- O^T += V^T P^T
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 pb;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[ks >> 1][8 * (ks & 1) + e];
-            const int i16 = lane & 15, g = (lane >> 4) & 1;
-            const int vrow = 16 * ks + 4 * hh + (i16 >> 2);
-            const int vcol = 16 * g + 4 * (i16 & 3);
-#pragma unroll
-            for (int db = 0; db < DBLK; ++db) {
-                lds_bf16x4* p0 = (lds_bf16x4*)((__attribute__((address_space(3))) uint16_t*)Vs +
-                                               vrow * VSTR + 32 * db + vcol);
-                lds_bf16x4* p1 = (lds_bf16x4*)((__attribute__((address_space(3))) uint16_t*)Vs +
-                                               (vrow + 8) * VSTR + 32 * db + vcol);
-                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(p0);
-                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(p1);
-                const bf16x8 vreg = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg, pb, oacc[db], 0, 0, 0);
+        if (STAGES == 1) {
+            __syncthreads();                                 // the single stage is free again
+            if (it + 1 < nt) {
+                const int t1 = t_begin + it + 1;
+                k0_next = a.col_idx[t1] * kBN;
+                issue_tile_loads<D, NW, false>(k_rsrc, lds, k0_next, sk_bytes, wave, lane);
+                issue_tile_loads<D, NW, true>(v_rsrc, lds + TILE, k0_next, sv_bytes, wave, lane);
+                word_next = a.bitmaps[(size_t)t1 * BM + brow];
             }
         }
     }
 
-    // ---- epilogue: normalise, write O (bf16, round to nearest even) and lse
+    // ---- epilogue: normalise, stage O through LDS, coalesced stores; lse
     const float ltot = lsum + __shfl_xor(lsum, 32, 64);
-    if (!row_ok) return;
     const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
-    uint16_t* orow = Op + (size_t)qrow * a.so[2];
+    __syncthreads();                                         // all wavefronts are done with K/V in LDS
+    uint16_t* ostage = smem + wave * 32 * D;                 // this wavefront's 32 rows
+    {
+        const int f = swz_k<D>(n);
 #pragma unroll
-    for (int db = 0; db < DBLK; ++db)
+        for (int db = 0; db < DBLK; ++db)
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-            uint2 w;
-            w.x = pack_bf16_rne(oacc[db][4 * g4] * inv, oacc[db][4 * g4 + 1] * inv);
-            w.y = pack_bf16_rne(oacc[db][4 * g4 + 2] * inv, oacc[db][4 * g4 + 3] * inv);
-            *reinterpret_cast<uint2*>(orow + 32 * db + 8 * g4 + 4 * hh) = w;
+            for (int g4 = 0; g4 < 4; ++g4) {
+                uint2 w;
+                w.x = pack_bf16_rne(oacc[db][4 * g4] * inv, oacc[db][4 * g4 + 1] * inv);
+                w.y = pack_bf16_rne(oacc[db][4 * g4 + 2] * inv, oacc[db][4 * g4 + 3] * inv);
+                const int chunk = (4 * db + g4) ^ f;
+                *reinterpret_cast<uint2*>(ostage + n * D + chunk * 8 + 4 * hh) = w;
+            }
+    }
+    // same wavefront reads back what it wrote: no barrier needed, only LDS ordering
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    {
+        const int row_base = qb * BM + wave * 32;
+#pragma unroll
+        for (int u = 0; u < (32 * CPR) / 64; ++u) {
+            const int idx = u * 64 + lane;
+            const int rr = idx / CPR, c = idx % CPR;
+            const uint4 v = *reinterpret_cast<const uint4*>(ostage + rr * D + (c ^ swz_k<D>(rr)) * 8);
+            if (row_base + rr < a.Lq)
+                *reinterpret_cast<uint4*>(Op + (size_t)(row_base + rr) * a.so[2] + c * 8) = v;
         }
-    if (a.lse && hh == 0)
+    }
+    if (a.lse && hh == 0 && row_ok)
         a.lse[((size_t)b * a.H + h) * a.Lq + qrow] =
             ltot > 0.f ? (m * sc + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
 }
 
-template <int D, int NW>
+template <int D, int NW, int STAGES>
 hipError_t launch_one(const FwdArgs& a, hipStream_t stream)
 {
     const int nQB = (a.Lq + 32 * NW - 1) / (32 * NW);
     const long long blocks = (long long)nQB * a.H * a.B;
-    hipLaunchKernelGGL((fwd_mfma_kernel<D, NW>), dim3((unsigned)blocks), dim3(64 * NW), 0, stream, a, nQB);
+    const int xcd_chunk = (blocks % 8 == 0) ? (int)(blocks / 8) : 0;
+    hipLaunchKernelGGL((fwd_mfma_kernel<D, NW, STAGES>), dim3((unsigned)blocks), dim3(64 * NW), 0,
+                       stream, a, nQB, xcd_chunk);
     return hipGetLastError();
 }
 
@@ -258,10 +351,16 @@ hipError_t launch_one(const FwdArgs& a, hipStream_t stream)
 hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream)
 {
     const bool wide = a.block_m == 128;
+    static const int tune_stages = getenv("AP_TUNE_STAGES") ? atoi(getenv("AP_TUNE_STAGES")) : 0;
+    const bool one = tune_stages == 1;
     switch (a.D) {
-    case 32: return wide ? launch_one<32, 4>(a, stream) : launch_one<32, 2>(a, stream);
-    case 64: return wide ? launch_one<64, 4>(a, stream) : launch_one<64, 2>(a, stream);
-    case 128: return wide ? launch_one<128, 4>(a, stream) : launch_one<128, 2>(a, stream);
+    case 32: return wide ? launch_one<32, 4, 2>(a, stream) : launch_one<32, 2, 2>(a, stream);
+    case 64:
+        if (one) return wide ? launch_one<64, 4, 1>(a, stream) : launch_one<64, 2, 1>(a, stream);
+        return wide ? launch_one<64, 4, 2>(a, stream) : launch_one<64, 2, 2>(a, stream);
+    case 128:
+        if (one) return wide ? launch_one<128, 4, 1>(a, stream) : launch_one<128, 2, 1>(a, stream);
+        return wide ? launch_one<128, 4, 2>(a, stream) : launch_one<128, 2, 2>(a, stream);
     default: return hipErrorInvalidValue;
     }
 }
