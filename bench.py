@@ -31,6 +31,8 @@ def parse():
     p.add_argument("--warmup", type=int, default=20)
     p.add_argument("--workload", default="C5", help="headline configuration (C1..C5)")
     p.add_argument("--block-m", type=int, default=64)
+    p.add_argument("--min-cols", type=int, default=0, help="schedule packing threshold (0 = library default)")
+    p.add_argument("--no-sched", action="store_true", help="walk the layout itself instead of the visit schedule")
     p.add_argument("--only", action="store_true", help="skip the per-config table and the CPU baseline")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     return p.parse_args()
@@ -83,14 +85,15 @@ def main():
         # rotate through enough independent sets that no call finds its inputs in the 256 MB cache
         return max(2, -(-2 * INFINITY_CACHE_BYTES // alg_bytes(cfg)) + 1)
 
-    def time_calls(cfg, layout, sets, outs, lses, steps, warmup):
+    def time_calls(cfg, layout, sets, outs, lses, steps, warmup, sched=None):
         """Exactly `steps` back-to-back launches on the current stream, one HIP event between
         each pair; returns (wall ms per step, list of per-launch ms)."""
         n = len(sets)
 
         def call(i):
             q, k, v = sets[i % n]
-            ap.ap_sparse_attn_fwd(q, k, v, layout, causal=cfg.causal, out=outs[i % n], lse=lses[i % n])
+            ap.ap_sparse_attn_fwd(q, k, v, layout, causal=cfg.causal, out=outs[i % n], lse=lses[i % n],
+                                  sched=sched)
 
         for i in range(warmup):
             call(i)
@@ -106,7 +109,7 @@ def main():
         per = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
         return wall_ms, per
 
-    def time_graph(cfg, layout, sets, outs, lses, steps, warmup):
+    def time_graph(cfg, layout, sets, outs, lses, steps, warmup, sched=None):
         """For microsecond-scale kernels the Python launch rate, not the GPU, would set the pace:
         capture one rotation through all sets into a HIP graph and time its replays."""
         n = len(sets)
@@ -115,14 +118,16 @@ def main():
         with torch.cuda.stream(side):
             for i in range(n):
                 q, k, v = sets[i]
-                ap.ap_sparse_attn_fwd(q, k, v, layout, causal=cfg.causal, out=outs[i], lse=lses[i])
+                ap.ap_sparse_attn_fwd(q, k, v, layout, causal=cfg.causal, out=outs[i], lse=lses[i],
+                                      sched=sched)
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             for i in range(n):
                 q, k, v = sets[i]
-                ap.ap_sparse_attn_fwd(q, k, v, layout, causal=cfg.causal, out=outs[i], lse=lses[i])
+                ap.ap_sparse_attn_fwd(q, k, v, layout, causal=cfg.causal, out=outs[i], lse=lses[i],
+                                      sched=sched)
         reps = max(1, -(-steps // n))
         for _ in range(max(1, warmup // n)):
             g.replay()
@@ -147,11 +152,21 @@ def main():
         torch.cuda.synchronize()
         layout_ms = e0.elapsed_time(e1)
         dense_layout = ap.ap_build_layout(torch.ones_like(dmask), block_m, 64)
+        sched = None
+        sched_ms = None
+        if cfg.dtype == "bf16" and not args.no_sched:
+            ap.ap_build_schedule(layout, causal=cfg.causal, min_cols=args.min_cols)
+            torch.cuda.synchronize()
+            e0.record()
+            sched = ap.ap_build_schedule(layout, causal=cfg.causal, min_cols=args.min_cols)
+            e1.record()
+            torch.cuda.synchronize()
+            sched_ms = e0.elapsed_time(e1)
         torch.cuda.synchronize()
         del dmask
 
         sets, outs, lses = tensor_sets(cfg, n_sets_for(cfg))
-        wall_ms, per = time_calls(cfg, layout, sets, outs, lses, steps, warmup)
+        wall_ms, per = time_calls(cfg, layout, sets, outs, lses, steps, warmup, sched)
         dsteps = max(10, steps // 4)
         dwall_ms, dper = time_calls(cfg, dense_layout, sets, outs, lses, dsteps, max(2, warmup // 4))
         ms = float(np.mean(per))
@@ -159,7 +174,7 @@ def main():
         gms = gdms = None
         if use_graph:
             try:
-                gms = time_graph(cfg, layout, sets, outs, lses, steps, warmup)
+                gms = time_graph(cfg, layout, sets, outs, lses, steps, warmup, sched)
                 gdms = time_graph(cfg, dense_layout, sets, outs, lses, dsteps, warmup)
             except Exception as ex:                                   # graph capture is an extra
                 log("graph timing unavailable:", repr(ex))
@@ -174,13 +189,16 @@ def main():
             dense_entries = cfg.H * cfg.Lq * cfg.Lk
         dense_flop = 4.0 * cfg.D * dense_entries * cfg.B
         nnz = int(layout.nnz.item())
-        tile_flop = 4.0 * cfg.D * block_m * 64 * nnz * cfg.B           # matrix-core work of the visited tiles
+        visited = int(sched.cnt.sum().item()) if sched is not None else nnz
+        tile_flop = 4.0 * cfg.D * block_m * 64 * visited * cfg.B           # matrix-core work of the visited tiles
         res = {
             "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D,
                       "dtype": cfg.dtype, "causal": cfg.causal},
             "kept_entries_per_batch": kept,
             "keep_density": kept / float(dense_entries),
             "tiles_stored": nnz,
+            "tiles_visited": visited,
+            "schedule_ms": sched_ms,
             "tiles_max": int(ap.ap_layout_max_tiles(cfg.H, cfg.Lq, cfg.Lk, block_m, 64)),
             "ms_per_call": kernel_ms,
             "ms_per_call_stream_launches": ms,
@@ -201,7 +219,7 @@ def main():
             "timing": "hip graph replay" if gms is not None else "stream launches",
             "n_buffer_sets": len(sets),
         }
-        keep_for_parity = (sets[0], outs, lses, layout)
+        keep_for_parity = (sets[0], outs, lses, layout, sched)
         return res, keep_for_parity
 
     # ---------------------------------------------------------------- headline workload
@@ -210,7 +228,7 @@ def main():
     head_mask = synth.make_mask(head)
     small = head.name != "C5"
     log("timing", head.name, "...")
-    head_res, (set0, outs, lses, layout) = run_config(head, head_mask, args.steps, args.warmup,
+    head_res, (set0, outs, lses, layout, sched) = run_config(head, head_mask, args.steps, args.warmup,
                                                      args.block_m, use_graph=small)
 
     # ---------------------------------------------------------------- CPU baseline = the oracle
@@ -219,7 +237,7 @@ def main():
     if not args.only and not args.no_cpu:
         import oracle
         q, k, v = set0
-        ap.ap_sparse_attn_fwd(q, k, v, layout, causal=head.causal, out=outs[0], lse=lses[0])
+        ap.ap_sparse_attn_fwd(q, k, v, layout, causal=head.causal, out=outs[0], lse=lses[0], sched=sched)
         torch.cuda.synchronize()
         rq, rk, rv = (x.to(torch.float64).cpu().numpy() for x in (q, k, v))
         log("timing the CPU oracle on the full", head.name, "workload ...")
@@ -234,7 +252,7 @@ def main():
                   "max_abs_err_lse": float(np.abs(lses[0].to(torch.float64).cpu().numpy() - lse_ref).max()),
                   "tolerance": 2e-2 if head.dtype == "bf16" else 1e-5}
         del rq, rk, rv, O_ref, lse_ref
-    del set0, outs, lses, layout
+    del set0, outs, lses, layout, sched
     torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- the other configurations
@@ -268,7 +286,7 @@ def main():
             head.name, head.B, head.H, head.Lq, head.Lk, head.D, head.dtype,
             "causal" if head.causal else "non-causal", 100 * head.keep,
             "causal" if head.causal else "all"),
-            "block_m": args.block_m, "block_n": 64},
+            "block_m": args.block_m, "block_n": 64, "visit_schedule": not args.no_sched},
         "ms_per_call": head_res["ms_per_call"],
         "speedup_vs_dense": head_res["speedup_vs_dense"],
         "layout_ms": head_res["layout_ms"],

@@ -99,6 +99,42 @@ ap_status ap_build_layout(const uint8_t *mask, int H, int Lq, int Lk, int block_
                           int64_t *nnz_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Visit schedule: an optional, derived re-packing of a layout for the attention kernel.
+ *
+ * A mask that keeps a band next to the diagonal (the constant context window that the figure of
+ * Section 5.1 shows for self-attention) plus scattered isolated connections has a kept entry in
+ * nearly every tile of a long sequence, although few tiles hold many.  The schedule lists, per block row, "entries" of 64 keys each: a stored tile whose visible part
+ * spans at least `min_cols` distinct key columns stays a run of 64 consecutive keys; the visible
+ * columns of all other tiles of the block row are packed, ascending, into gathered entries of 64
+ * arbitrary keys.  The causal limit (if any) is folded into the entry bitmaps, so a schedule must
+ * be used with the same `causal` flag and the same layout it was built from.  It is a pure
+ * function of its inputs (fixed order, no atomics) and never changes which (query, key) pairs
+ * are evaluated -- only how they are grouped.
+ *
+ * Entry e of block row r is element row_ptr[r] + e of the arrays below; a block row never has
+ * more entries than stored tiles, so arrays sized for the layout's `cap` always suffice.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct ap_schedule {
+    int32_t *cnt;      /* device int32 [H*nQB]        number of entries of each block row           */
+    int32_t *start;    /* device int32 [cap]          >= 0: first key of 64 consecutive keys;
+                                                      -1: gathered entry, keys listed in cols       */
+    int32_t *cols;     /* device int32 [cap*64]       key index per slot of a gathered entry; empty
+                                                      slots hold Lk                                 */
+    uint64_t *bitmaps; /* device uint64 [cap*block_m] bit c of row rr: slot c of the entry is kept  */
+} ap_schedule;
+
+/*
+ * Build the schedule of a layout (block_n must be 64, block_m 64 or 128).  `cap` is the number of
+ * tiles the layout arrays and the schedule arrays have room for (>= the layout's nnz).
+ * min_cols in [1, 65]: 1 keeps every tile as it is, 65 gathers everything; 0 selects the default.
+ * All pointers inside `sched` (a host struct of device pointers) must be non-null and 8-byte
+ * aligned for bitmaps, 4-byte for the rest.  Asynchronous on `stream`.
+ */
+ap_status ap_build_schedule(const int32_t *row_ptr, const int32_t *col_idx, const uint64_t *bitmaps,
+                            int H, int Lq, int Lk, int block_m, int block_n, int64_t cap, int causal,
+                            int min_cols, const ap_schedule *sched, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Masked attention forward (Section 3.2, masked-attention equation).
  *
  * For every batch b, head h and query i, over the keys j with mask[h,i,j] != 0 (and, if
@@ -119,6 +155,8 @@ ap_status ap_build_layout(const uint8_t *mask, int H, int Lq, int Lk, int block_
  *   lse           out, float [B, H, Lq] contiguous, or NULL
  *   row_ptr, col_idx, bitmaps   layout from ap_build_layout with the same H, Lq, Lk, block_m,
  *                 block_n; read-only, reusable across any number of calls
+ *   sched         NULL, or a schedule built from this layout with the same `causal` (host
+ *                 pointer to a struct of device pointers); bf16 only
  *   causal        nonzero = also hide future keys; requires Lk >= Lq
  *   softmax_scale <= 0 selects 1/sqrt(D)
  *
@@ -131,7 +169,8 @@ ap_status ap_sparse_attn_fwd(const void *Q, const void *K, const void *V, void *
                              const int64_t *stride_v, const int64_t *stride_o,
                              const int32_t *row_ptr, const int32_t *col_idx,
                              const uint64_t *bitmaps, int block_m, int block_n,
-                             int causal, float softmax_scale, void *stream);
+                             const ap_schedule *sched, int causal, float softmax_scale,
+                             void *stream);
 
 #ifdef __cplusplus
 }

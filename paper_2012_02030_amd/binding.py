@@ -24,7 +24,13 @@ AP_F32 = 0
 AP_BF16 = 1
 
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
-           "ap_build_layout", "ap_sparse_attn_fwd")
+           "ap_build_layout", "ap_build_schedule", "ap_sparse_attn_fwd")
+
+
+class _CSchedule(ctypes.Structure):
+    """struct ap_schedule: four device pointers."""
+    _fields_ = [("cnt", ctypes.c_void_p), ("start", ctypes.c_void_p), ("cols", ctypes.c_void_p),
+                ("bitmaps", ctypes.c_void_p)]
 
 _lib = None
 
@@ -54,11 +60,15 @@ def lib() -> ctypes.CDLL:
         L.ap_build_layout.restype = i32
         L.ap_build_layout.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp,
                                       ctypes.c_size_t, vp]
+        L.ap_build_schedule.restype = i32
+        L.ap_build_schedule.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i64, i32, i32,
+                                        ctypes.POINTER(_CSchedule), vp]
         L.ap_sparse_attn_fwd.restype = i32
         L.ap_sparse_attn_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
                                          ctypes.POINTER(i64), ctypes.POINTER(i64),
                                          ctypes.POINTER(i64), ctypes.POINTER(i64),
-                                         vp, vp, vp, i32, i32, i32, ctypes.c_float, vp]
+                                         vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
+                                         ctypes.c_float, vp]
         _lib = L
     return _lib
 
@@ -133,6 +143,41 @@ def ap_build_layout(mask: torch.Tensor, block_m: int = 64, block_n: int = 64,
     return Layout(row_ptr, col_idx, bitmaps, nnz, H, Lq, Lk, block_m, block_n)
 
 
+class Schedule(NamedTuple):
+    """Device arrays of a visit schedule (see ap_schedule in include/ap.h)."""
+    cnt: torch.Tensor        # int32 [H*nQB]
+    start: torch.Tensor      # int32 [cap]
+    cols: torch.Tensor       # int32 [cap, 64]
+    bitmaps: torch.Tensor    # int64 storage of uint64 words [cap, block_m]
+    causal: bool
+    min_cols: int
+
+    def c_struct(self) -> _CSchedule:
+        return _CSchedule(self.cnt.data_ptr(), self.start.data_ptr(), self.cols.data_ptr(),
+                          self.bitmaps.data_ptr())
+
+
+def ap_build_schedule(layout: Layout, causal: bool = False, min_cols: int = 0,
+                      stream: Optional[torch.cuda.Stream] = None) -> Schedule:
+    """Derive the visit schedule of a layout (block_n = 64).  Asynchronous on the stream."""
+    dev = layout.row_ptr.device
+    cap = int(layout.col_idx.shape[0])
+    nrows = int(layout.row_ptr.shape[0]) - 1
+    sched = Schedule(torch.empty(nrows, dtype=torch.int32, device=dev),
+                     torch.empty(cap, dtype=torch.int32, device=dev),
+                     torch.empty((cap, 64), dtype=torch.int32, device=dev),
+                     torch.empty((cap, layout.block_m), dtype=torch.int64, device=dev),
+                     bool(causal), int(min_cols))
+    cs = sched.c_struct()
+    st = lib().ap_build_schedule(layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(),
+                                 layout.bitmaps.data_ptr(), layout.H, layout.Lq, layout.Lk,
+                                 layout.block_m, layout.block_n, cap, int(bool(causal)), int(min_cols),
+                                 ctypes.byref(cs), _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_build_schedule")
+    return sched
+
+
 def _strides3(t: torch.Tensor):
     return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
 
@@ -140,7 +185,8 @@ def _strides3(t: torch.Tensor):
 def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout: Layout,
                        causal: bool = False, softmax_scale: float = 0.0,
                        out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
-                       return_lse: bool = True, stream: Optional[torch.cuda.Stream] = None):
+                       return_lse: bool = True, stream: Optional[torch.cuda.Stream] = None,
+                       sched: Optional[Schedule] = None):
     """Q [B,H,Lq,D], K/V [B,H,Lk,D] device tensors (fp32 or bf16, last dim contiguous).
 
     Returns (O, lse); lse is None when return_lse is False.  Asynchronous on the stream.
@@ -164,6 +210,9 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
     for t in (Q, K, V):
         if t.stride(3) != 1:
             raise ValueError("last dimension must be contiguous")
+    if sched is not None and sched.causal != bool(causal):
+        raise ValueError("schedule was built with causal=%s" % sched.causal)
+    cs = sched.c_struct() if sched is not None else None
     if out is None:
         out = torch.empty((B, H, Lq, D), dtype=Q.dtype, device=Q.device)
     if lse is None and return_lse:
@@ -173,8 +222,8 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
         lse.data_ptr() if lse is not None else None, dt, B, H, Lq, Lk, D,
         _strides3(Q), _strides3(K), _strides3(V), _strides3(out),
         layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
-        layout.block_m, layout.block_n, int(bool(causal)), float(softmax_scale),
-        _stream_ptr(stream))
+        layout.block_m, layout.block_n, ctypes.byref(cs) if cs is not None else None,
+        int(bool(causal)), float(softmax_scale), _stream_ptr(stream))
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_fwd")
     return out, lse

@@ -68,13 +68,34 @@ ap_status ap_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int block_
     return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
+ap_status ap_build_schedule(const int32_t* row_ptr, const int32_t* col_idx, const uint64_t* bitmaps,
+                            int H, int Lq, int Lk, int block_m, int block_n, int64_t cap, int causal,
+                            int min_cols, const ap_schedule* sched, void* stream)
+{
+    if (!row_ptr || !col_idx || !bitmaps || !sched) return AP_ERR_INVALID_ARG;
+    if (!sched->cnt || !sched->start || !sched->cols || !sched->bitmaps) return AP_ERR_INVALID_ARG;
+    if (H <= 0 || Lq <= 0 || Lk <= 0 || cap < 0) return AP_ERR_INVALID_ARG;
+    if (causal && Lk < Lq) return AP_ERR_INVALID_ARG;
+    if (min_cols < 0 || min_cols > 65) return AP_ERR_INVALID_ARG;
+    if (block_n != 64 || !(block_m == 64 || block_m == 128)) return AP_ERR_UNSUPPORTED;
+    if (!ap::layout_shape_ok(H, Lq, Lk, block_m, block_n)) return AP_ERR_UNSUPPORTED;
+    if (!aligned(row_ptr, 4) || !aligned(col_idx, 4) || !aligned(bitmaps, 8) || !aligned(sched->cnt, 4) ||
+        !aligned(sched->start, 4) || !aligned(sched->cols, 4) || !aligned(sched->bitmaps, 8))
+        return AP_ERR_INVALID_ARG;
+    ap::Schedule s{sched->cnt, sched->start, sched->cols, sched->bitmaps};
+    const hipError_t e = ap::launch_build_schedule(row_ptr, col_idx, bitmaps, H, Lq, Lk, block_m,
+                                                   (long long)cap, causal ? 1 : 0, min_cols == 0 ? 48 : min_cols, s,
+                                                   (hipStream_t)stream);
+    return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
 ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* lse,
                              ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
                              const int64_t* stride_q, const int64_t* stride_k,
                              const int64_t* stride_v, const int64_t* stride_o,
                              const int32_t* row_ptr, const int32_t* col_idx,
-                             const uint64_t* bitmaps, int block_m, int block_n, int causal,
-                             float softmax_scale, void* stream)
+                             const uint64_t* bitmaps, int block_m, int block_n,
+                             const ap_schedule* sched, int causal, float softmax_scale, void* stream)
 {
     if (!Q || !K || !V || !O || !stride_q || !stride_k || !stride_v || !stride_o || !row_ptr ||
         !col_idx || !bitmaps)
@@ -86,6 +107,13 @@ ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* 
     if (O == Q || O == K || O == V) return AP_ERR_INVALID_ARG;
     if (isnan(softmax_scale) || isinf(softmax_scale)) return AP_ERR_INVALID_ARG;
 
+    if (sched) {
+        if (!sched->cnt || !sched->start || !sched->cols || !sched->bitmaps) return AP_ERR_INVALID_ARG;
+        if (!aligned(sched->cnt, 4) || !aligned(sched->start, 4) || !aligned(sched->cols, 4) ||
+            !aligned(sched->bitmaps, 8))
+            return AP_ERR_INVALID_ARG;
+        if (dtype != AP_BF16) return AP_ERR_UNSUPPORTED;
+    }
     if (!(D == 32 || D == 64 || D == 128)) return AP_ERR_UNSUPPORTED;
     if (block_n != 64) return AP_ERR_UNSUPPORTED;
     if (!(block_m == 64 || (block_m == 128 && dtype == AP_BF16))) return AP_ERR_UNSUPPORTED;
@@ -115,6 +143,10 @@ ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* 
     a.block_m = block_m; a.block_n = block_n;
     a.causal = causal ? 1 : 0;
     a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+    if (sched)
+        a.sched = ap::Schedule{sched->cnt, sched->start, sched->cols, sched->bitmaps};
+    else
+        a.sched = ap::Schedule{nullptr, nullptr, nullptr, nullptr};
 
     hipError_t e;
     if (dtype == AP_BF16)

@@ -32,7 +32,6 @@
 // consecutive columns of row j, lane i ends up with column i of rows 0..3.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "ap_internal.h"
 
@@ -94,7 +93,32 @@ __device__ __forceinline__ void issue_tile_loads(__amdgpu_buffer_rsrc_t rsrc, ld
     }
 }
 
-template <int D, int NW, int STAGES>
+// Same for a gathered entry: row u of this lane's instructions comes from key gidx[u]
+// (an empty slot holds Lk, which lies beyond num_records and reads as zeros).
+template <int D, int NW, bool IS_V>
+__device__ __forceinline__ void issue_gather_loads(__amdgpu_buffer_rsrc_t rsrc, lds_u16* dst,
+                                                   const int* gidx, int stride_bytes, int wave,
+                                                   int lane)
+{
+    constexpr int CPR = D / 8;
+    constexpr int RPI = 64 / CPR;
+    constexpr int NI = kBN / RPI;
+    const int rl = lane / CPR;
+    const int cp = lane % CPR;
+#pragma unroll
+    for (int u = 0; u < NI / NW; ++u) {
+        const int j = wave + NW * u;
+        const int r = j * RPI + rl;
+        const int c = cp ^ (IS_V ? swz_v<D>(r) : swz_k<D>(r));
+        const int voff = gidx[u] * stride_bytes + c * 16;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(dst + j * 512), 16, voff, 0, 0, 0);
+    }
+}
+
+// SCHED = false: walk the stored tiles of the layout (64 consecutive keys each, causal limit
+// applied here).  SCHED = true: walk the entries of a visit schedule (consecutive or gathered
+// keys, causal limit already folded into the bitmaps).
+template <int D, int NW, int STAGES, bool SCHED>
 __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB, int xcd_chunk)
 {
     constexpr int BM = 32 * NW;
@@ -109,7 +133,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
     lds_u16* lds = (lds_u16*)smem;
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
     const int lane = tid & 63;
     const int n = lane & 31;                                 // query inside the wavefront's 32
     const int hh = lane >> 5;                                // which half of the key slots
@@ -157,13 +181,37 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
 
     const int r = h * nQB + qb;
     const int t_begin = a.row_ptr[r];
-    int nt = a.row_ptr[r + 1] - t_begin;
+    int nt = SCHED ? a.sched.cnt[r] : a.row_ptr[r + 1] - t_begin;
     const long long off = (long long)a.Lk - a.Lq;
     const long long diag = (long long)qrow + off;            // last visible key if causal
-    if (a.causal) {                                          // drop tiles that are entirely in the future
+    if (!SCHED && a.causal) {                                // drop tiles that are entirely in the future
         const long long block_diag = (long long)qb * BM + (BM - 1) + off;
         while (nt > 0 && (long long)a.col_idx[t_begin + nt - 1] * kBN > block_diag) --nt;
     }
+    const uint64_t* words = SCHED ? a.sched.bitmaps : a.bitmaps;
+    constexpr int NLOAD = (D / 8) / NW;                      // load instructions per wavefront and operand
+    constexpr int RPI = 64 / (D / 8);                        // tile rows per load instruction
+    const int g_row = lane / (D / 8);                        // this lane's row inside a load instruction
+
+    // first key of tile i of this block row (>= 0), or -1 for a gathered entry
+    auto tile_start = [&](int i) -> int {
+        return SCHED ? a.sched.start[t_begin + i] : a.col_idx[t_begin + i] * kBN;
+    };
+    // keys of the rows this lane loads, for a gathered entry
+    auto load_gather_idx = [&](int i, int* gidx) {
+#pragma unroll
+        for (int u = 0; u < NLOAD; ++u)
+            gidx[u] = a.sched.cols[(size_t)(t_begin + i) * 64 + (wave + NW * u) * RPI + g_row];
+    };
+    auto issue_tile = [&](int start, const int* gidx, lds_u16* Kd) {
+        if (!SCHED || start >= 0) {
+            issue_tile_loads<D, NW, false>(k_rsrc, Kd, start, sk_bytes, wave, lane);
+            issue_tile_loads<D, NW, true>(v_rsrc, Kd + TILE, start, sv_bytes, wave, lane);
+        } else {
+            issue_gather_loads<D, NW, false>(k_rsrc, Kd, gidx, sk_bytes, wave, lane);
+            issue_gather_loads<D, NW, true>(v_rsrc, Kd + TILE, gidx, sv_bytes, wave, lane);
+        }
+    };
 
     // per-lane LDS read offsets (elements), loop invariant
     const int k_swz = (hh ^ swz_k<D>(n));                    // rows n and n + 32 share the swizzle
@@ -173,14 +221,25 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
     const int v_chunk_lo = 2 * g + ((i16 >> 1) & 1);
     const int v_swz = swz_v<D>(vj) >> 2;                     // xor on the 4-chunk group index
 
-    // first tile
+    // first tile; the start (and gather keys) of the tile after it are fetched one step ahead
     uint64_t word_next = 0;
-    int k0_next = 0;
+    int k0_next = 0;                                         // start of the tile whose loads were issued last
+    int start_ahead = 0;                                     // start of the tile after that
+    int gidx[NLOAD];
+#pragma unroll
+    for (int u = 0; u < NLOAD; ++u) gidx[u] = 0;
     if (nt > 0) {
-        k0_next = a.col_idx[t_begin] * kBN;
-        issue_tile_loads<D, NW, false>(k_rsrc, lds, k0_next, sk_bytes, wave, lane);
-        issue_tile_loads<D, NW, true>(v_rsrc, lds + TILE, k0_next, sv_bytes, wave, lane);
-        word_next = a.bitmaps[(size_t)t_begin * BM + brow];
+        k0_next = tile_start(0);
+        if (SCHED && k0_next < 0) {
+            load_gather_idx(0, gidx);
+            wait_vmem();
+        }
+        issue_tile(k0_next, gidx, lds);
+        word_next = words[(size_t)t_begin * BM + brow];
+        if (nt > 1) {
+            start_ahead = tile_start(1);
+            if (SCHED && start_ahead < 0) load_gather_idx(1, gidx);
+        }
     }
 
     for (int it = 0; it < nt; ++it) {
@@ -193,15 +252,16 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
         wait_vmem();                                         // my loads of this tile have landed
         __syncthreads();                                     // ... and everybody else's
         if (STAGES == 2 && it + 1 < nt) {
-            const int t1 = t_begin + it + 1;
-            k0_next = a.col_idx[t1] * kBN;
-            lds_u16* Kn = lds + (stage ^ 1) * 2 * TILE;
-            issue_tile_loads<D, NW, false>(k_rsrc, Kn, k0_next, sk_bytes, wave, lane);
-            issue_tile_loads<D, NW, true>(v_rsrc, Kn + TILE, k0_next, sv_bytes, wave, lane);
-            word_next = a.bitmaps[(size_t)t1 * BM + brow];
+            k0_next = start_ahead;
+            issue_tile(k0_next, gidx, lds + (stage ^ 1) * 2 * TILE);
+            word_next = words[(size_t)(t_begin + it + 1) * BM + brow];
+            if (it + 2 < nt) {
+                start_ahead = tile_start(it + 2);
+                if (SCHED && start_ahead < 0) load_gather_idx(it + 2, gidx);
+            }
         }
 
-        if (a.causal) {
+        if (!SCHED && a.causal) {
             const long long lim = diag - k0;
             if (lim < 0) word = 0;
             else if (lim < 63) word &= (2ull << lim) - 1ull;
@@ -290,11 +350,13 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
         if (STAGES == 1) {
             __syncthreads();                                 // the single stage is free again
             if (it + 1 < nt) {
-                const int t1 = t_begin + it + 1;
-                k0_next = a.col_idx[t1] * kBN;
-                issue_tile_loads<D, NW, false>(k_rsrc, lds, k0_next, sk_bytes, wave, lane);
-                issue_tile_loads<D, NW, true>(v_rsrc, lds + TILE, k0_next, sv_bytes, wave, lane);
-                word_next = a.bitmaps[(size_t)t1 * BM + brow];
+                k0_next = start_ahead;
+                issue_tile(k0_next, gidx, lds);
+                word_next = words[(size_t)(t_begin + it + 1) * BM + brow];
+                if (it + 2 < nt) {
+                    start_ahead = tile_start(it + 2);
+                    if (SCHED && start_ahead < 0) load_gather_idx(it + 2, gidx);
+                }
             }
         }
     }
@@ -341,8 +403,12 @@ hipError_t launch_one(const FwdArgs& a, hipStream_t stream)
     const int nQB = (a.Lq + 32 * NW - 1) / (32 * NW);
     const long long blocks = (long long)nQB * a.H * a.B;
     const int xcd_chunk = (blocks % 8 == 0) ? (int)(blocks / 8) : 0;
-    hipLaunchKernelGGL((fwd_mfma_kernel<D, NW, STAGES>), dim3((unsigned)blocks), dim3(64 * NW), 0,
-                       stream, a, nQB, xcd_chunk);
+    if (a.sched.cnt)
+        hipLaunchKernelGGL((fwd_mfma_kernel<D, NW, STAGES, true>), dim3((unsigned)blocks),
+                           dim3(64 * NW), 0, stream, a, nQB, xcd_chunk);
+    else
+        hipLaunchKernelGGL((fwd_mfma_kernel<D, NW, STAGES, false>), dim3((unsigned)blocks),
+                           dim3(64 * NW), 0, stream, a, nQB, xcd_chunk);
     return hipGetLastError();
 }
 
@@ -350,17 +416,14 @@ hipError_t launch_one(const FwdArgs& a, hipStream_t stream)
 
 hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream)
 {
+    // 64-query block rows: two wavefronts and one LDS stage (32 KB at D = 128), so that four
+    // workgroups share a CU and hide each other's load latency.  128-query block rows: four
+    // wavefronts and two LDS stages, two workgroups per CU.
     const bool wide = a.block_m == 128;
-    static const int tune_stages = getenv("AP_TUNE_STAGES") ? atoi(getenv("AP_TUNE_STAGES")) : 0;
-    const bool one = tune_stages == 1;
     switch (a.D) {
-    case 32: return wide ? launch_one<32, 4, 2>(a, stream) : launch_one<32, 2, 2>(a, stream);
-    case 64:
-        if (one) return wide ? launch_one<64, 4, 1>(a, stream) : launch_one<64, 2, 1>(a, stream);
-        return wide ? launch_one<64, 4, 2>(a, stream) : launch_one<64, 2, 2>(a, stream);
-    case 128:
-        if (one) return wide ? launch_one<128, 4, 1>(a, stream) : launch_one<128, 2, 1>(a, stream);
-        return wide ? launch_one<128, 4, 2>(a, stream) : launch_one<128, 2, 2>(a, stream);
+    case 32: return wide ? launch_one<32, 4, 2>(a, stream) : launch_one<32, 2, 1>(a, stream);
+    case 64: return wide ? launch_one<64, 4, 2>(a, stream) : launch_one<64, 2, 1>(a, stream);
+    case 128: return wide ? launch_one<128, 4, 2>(a, stream) : launch_one<128, 2, 1>(a, stream);
     default: return hipErrorInvalidValue;
     }
 }

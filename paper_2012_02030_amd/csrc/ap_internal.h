@@ -15,6 +15,18 @@ hipError_t launch_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int B
                                long long cap, int64_t* nnz_out, void* workspace,
                                hipStream_t stream);
 
+// ---- visit schedule (ap_schedule.hip): entry e of block row r is element row_ptr[r] + e
+struct Schedule {
+    int32_t* cnt;        // [H*nQB]      entries of each block row
+    int32_t* start;      // [cap]        >= 0: first key of 64 consecutive keys; -1: gathered keys
+    int32_t* cols;       // [cap*64]     key of every slot of a gathered entry (Lk = empty slot)
+    uint64_t* bitmaps;   // [cap*BM]     bit c of row rr: slot c kept (causal limit folded in)
+};
+hipError_t launch_build_schedule(const int32_t* row_ptr, const int32_t* col_idx,
+                                 const uint64_t* bitmaps, int H, int Lq, int Lk, int BM,
+                                 long long cap, int causal, int min_cols, const Schedule& s,
+                                 hipStream_t stream);
+
 // ---- attention forward (ap_attn_valu.hip, ap_attn_mfma.hip)
 struct FwdArgs {
     const void* Q;
@@ -30,6 +42,7 @@ struct FwdArgs {
     int block_m, block_n;
     int causal;
     float scale;                    // already resolved (> 0)
+    Schedule sched;                 // all null: walk the layout itself
 };
 
 // fp32-arithmetic kernel (one query per lane); handles fp32 and bf16 storage, block 64x64

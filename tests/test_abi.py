@@ -76,7 +76,7 @@ def _fwd(L, **over):
     return L.ap_sparse_attn_fwd(a["Q"], a["K"], a["V"], a["O"], a["lse"], a["dtype"], a["B"], a["H"],
                                 a["Lq"], a["Lk"], a["D"], a["sq"], a["sk"], a["sv"], a["so"],
                                 a["row_ptr"], a["col_idx"], a["bitmaps"], a["bm"], a["bn"],
-                                a["causal"], a["scale"], None)
+                                a.get("sched"), a["causal"], a["scale"], None)
 
 
 def test_fwd_rejects_bad_arguments(L):
@@ -97,6 +97,24 @@ def test_fwd_rejects_bad_arguments(L):
     short = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 32)
     assert _fwd(L, sv=short) == ap.AP_ERR_INVALID_ARG                          # row stride < D
     assert _fwd(L, scale=float("nan")) == ap.AP_ERR_INVALID_ARG
+
+
+def test_schedule_arguments(L):
+    fake = 0x1000
+    good = ap._CSchedule(fake, fake, fake, fake)
+    call = L.ap_build_schedule
+    import ctypes as C
+    assert call(fake, fake, fake, 2, 64, 64, 64, 64, 8, 0, 0, None, None) == ap.AP_ERR_INVALID_ARG
+    assert call(None, fake, fake, 2, 64, 64, 64, 64, 8, 0, 0, C.byref(good), None) == ap.AP_ERR_INVALID_ARG
+    assert call(fake, fake, fake, 2, 64, 64, 32, 64, 8, 0, 0, C.byref(good), None) == ap.AP_ERR_UNSUPPORTED
+    assert call(fake, fake, fake, 2, 64, 64, 64, 32, 8, 0, 0, C.byref(good), None) == ap.AP_ERR_UNSUPPORTED
+    assert call(fake, fake, fake, 2, 64, 64, 64, 64, 8, 0, 66, C.byref(good), None) == ap.AP_ERR_INVALID_ARG
+    assert call(fake, fake, fake, 2, 128, 64, 64, 64, 8, 1, 0, C.byref(good), None) == ap.AP_ERR_INVALID_ARG
+    hole = ap._CSchedule(fake, None, fake, fake)
+    assert call(fake, fake, fake, 2, 64, 64, 64, 64, 8, 0, 0, C.byref(hole), None) == ap.AP_ERR_INVALID_ARG
+    # forward: a schedule needs bf16 and complete pointers
+    assert _fwd(L, sched=C.pointer(hole)) == ap.AP_ERR_INVALID_ARG
+    assert _fwd(L, sched=C.pointer(good), dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
 
 
 def test_missing_library_fails_loudly(monkeypatch):
