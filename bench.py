@@ -35,6 +35,8 @@ def parse():
     p.add_argument("--no-sched", action="store_true", help="walk the layout itself instead of the visit schedule")
     p.add_argument("--only", action="store_true", help="skip the per-config table and the CPU baseline")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    p.add_argument("--copy-calibration", action="store_true",
+                   help="also launch one plain 256 MiB device copy (reference point for HBM byte counters)")
     return p.parse_args()
 
 
@@ -221,6 +223,16 @@ def main():
         }
         keep_for_parity = (sets[0], outs, lses, layout, sched)
         return res, keep_for_parity
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)                                 # plain elementwise copy kernel: 256 MiB in, 256 MiB out
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- headline workload
     head = synth.CONFIGS[args.workload]

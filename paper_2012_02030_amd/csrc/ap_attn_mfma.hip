@@ -416,13 +416,13 @@ hipError_t launch_one(const FwdArgs& a, hipStream_t stream)
 
 hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream)
 {
-    // 64-query block rows: two wavefronts and one LDS stage (32 KB at D = 128), so that four
-    // workgroups share a CU and hide each other's load latency.  128-query block rows: four
-    // wavefronts and two LDS stages, two workgroups per CU.
+    // 64-query block rows: two wavefronts and at most 32 KB of LDS (one stage at D = 128, two
+    // below), so that four workgroups share a CU and hide each other's load latency.
+    // 128-query block rows: four wavefronts and two LDS stages, two workgroups per CU.
     const bool wide = a.block_m == 128;
     switch (a.D) {
-    case 32: return wide ? launch_one<32, 4, 2>(a, stream) : launch_one<32, 2, 1>(a, stream);
-    case 64: return wide ? launch_one<64, 4, 2>(a, stream) : launch_one<64, 2, 1>(a, stream);
+    case 32: return wide ? launch_one<32, 4, 2>(a, stream) : launch_one<32, 2, 2>(a, stream);
+    case 64: return wide ? launch_one<64, 4, 2>(a, stream) : launch_one<64, 2, 2>(a, stream);
     case 128: return wide ? launch_one<128, 4, 2>(a, stream) : launch_one<128, 2, 1>(a, stream);
     default: return hipErrorInvalidValue;
     }
