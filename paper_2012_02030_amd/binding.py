@@ -13,7 +13,8 @@ from typing import NamedTuple, Optional
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libap_mi355x.so")
+# AP_LIBRARY_PATH selects another build of the same library (e.g. one compiled with other flags)
+LIB_PATH = os.environ.get("AP_LIBRARY_PATH") or os.path.join(_PKG, "libap_mi355x.so")
 
 AP_OK = 0
 AP_ERR_INVALID_ARG = -1
@@ -31,6 +32,7 @@ class _CSchedule(ctypes.Structure):
     """struct ap_schedule: four device pointers."""
     _fields_ = [("cnt", ctypes.c_void_p), ("start", ctypes.c_void_p), ("cols", ctypes.c_void_p),
                 ("bitmaps", ctypes.c_void_p)]
+
 
 _lib = None
 

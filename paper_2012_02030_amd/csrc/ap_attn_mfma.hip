@@ -69,36 +69,60 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
 
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// One 128-bit buffer load per lane whose data goes straight to LDS: lane l's 16 bytes land at
+// lds_addr + 16*l.  lds_addr (a byte address, wave-uniform) travels in M0.  The instruction is
+// written as inline assembly on purpose: the compiler then does not know that LDS is being
+// written asynchronously, so it does not make every later LDS read wait for all loads in
+// flight; completion is enforced by wait_vmem() and the workgroup barrier in the main loop.
+typedef __attribute__((ext_vector_type(4))) int rsrc_t;
+__device__ __forceinline__ void load16_to_lds(unsigned lds_addr, int voff, rsrc_t rsrc, int soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+
+// Raw buffer descriptor: base address, stride 0, num_records bytes; loads beyond num_records
+// return zeros.
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned num_bytes)
+{
+    rsrc_t r;
+    r.x = (int)(uintptr_t)base;
+    r.y = (int)(((uintptr_t)base >> 32) & 0xffffu);
+    r.z = (int)num_bytes;
+    r.w = 0x00020000;
+    return r;
+}
+
+__device__ __forceinline__ unsigned lds_addr_of(lds_u16* p) { return (unsigned)(uintptr_t)p; }
+
 // Issue the loads of one 64-row tile (rows row0.. of a [rows, D] bf16 slice described by the
 // buffer resource) into LDS.  Every wavefront instruction moves 64 x 16 bytes = 1 KB.
 template <int D, int NW, bool IS_V>
-__device__ __forceinline__ void issue_tile_loads(__amdgpu_buffer_rsrc_t rsrc, lds_u16* dst,
-                                                 int row0, int stride_bytes, int wave, int lane)
+__device__ __forceinline__ void issue_tile_loads(rsrc_t rsrc, lds_u16* dst, int row0,
+                                                 int stride_bytes, int wave, int lane)
 {
     constexpr int CPR = D / 8;                // 16-byte chunks per row
     constexpr int RPI = 64 / CPR;             // rows per wavefront instruction
     constexpr int NI = kBN / RPI;             // instructions per tile
-    static_assert(NI % NW == 0 || NI < NW, "instructions must divide over the wavefronts");
+    static_assert(NI % NW == 0, "instructions must divide over the wavefronts");
     const int rl = lane / CPR;                // row inside the instruction
     const int cp = lane % CPR;                // chunk position in LDS
 #pragma unroll
-    for (int u = 0; u < (NI + NW - 1) / NW; ++u) {
+    for (int u = 0; u < NI / NW; ++u) {
         const int j = wave + NW * u;
-        if (NI < NW && j >= NI) break;        // wave-uniform
         const int r = j * RPI + rl;           // row inside the tile
         const int c = cp ^ (IS_V ? swz_v<D>(r) : swz_k<D>(r));
         const int voff = rl * stride_bytes + c * 16;
         const int soff = (row0 + j * RPI) * stride_bytes;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(dst + j * 512), 16, voff, soff, 0, 0);
+        load16_to_lds(lds_addr_of(dst + j * 512), voff, rsrc, soff);
     }
 }
 
 // Same for a gathered entry: row u of this lane's instructions comes from key gidx[u]
 // (an empty slot holds Lk, which lies beyond num_records and reads as zeros).
 template <int D, int NW, bool IS_V>
-__device__ __forceinline__ void issue_gather_loads(__amdgpu_buffer_rsrc_t rsrc, lds_u16* dst,
-                                                   const int* gidx, int stride_bytes, int wave,
-                                                   int lane)
+__device__ __forceinline__ void issue_gather_loads(rsrc_t rsrc, lds_u16* dst, const int* gidx,
+                                                   int stride_bytes, int wave, int lane)
 {
     constexpr int CPR = D / 8;
     constexpr int RPI = 64 / CPR;
@@ -111,7 +135,7 @@ __device__ __forceinline__ void issue_gather_loads(__amdgpu_buffer_rsrc_t rsrc, 
         const int r = j * RPI + rl;
         const int c = cp ^ (IS_V ? swz_v<D>(r) : swz_k<D>(r));
         const int voff = gidx[u] * stride_bytes + c * 16;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(dst + j * 512), 16, voff, 0, 0, 0);
+        load16_to_lds(lds_addr_of(dst + j * 512), voff, rsrc, 0);
     }
 }
 
@@ -152,10 +176,8 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
     uint16_t* Op = (uint16_t*)a.O + (size_t)b * a.so[0] + (size_t)h * a.so[1];
     const int sk_bytes = (int)a.sk[2] * 2, sv_bytes = (int)a.sv[2] * 2;
     // rows >= Lk lie beyond num_records: the hardware returns zeros for them
-    const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)Kp, 0, (a.Lk - 1) * sk_bytes + D * 2, 0x00020000);
-    const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)Vp, 0, (a.Lk - 1) * sv_bytes + D * 2, 0x00020000);
+    const rsrc_t k_rsrc = make_rsrc(Kp, (unsigned)((a.Lk - 1) * sk_bytes + D * 2));
+    const rsrc_t v_rsrc = make_rsrc(Vp, (unsigned)((a.Lk - 1) * sv_bytes + D * 2));
 
     const int brow = wave * 32 + n;                          // row inside the block row
     const int qrow = qb * BM + brow;                         // this lane's query
@@ -184,18 +206,46 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
     int nt = SCHED ? a.sched.cnt[r] : a.row_ptr[r + 1] - t_begin;
     const long long off = (long long)a.Lk - a.Lq;
     const long long diag = (long long)qrow + off;            // last visible key if causal
-    if (!SCHED && a.causal) {                                // drop tiles that are entirely in the future
-        const long long block_diag = (long long)qb * BM + (BM - 1) + off;
-        while (nt > 0 && (long long)a.col_idx[t_begin + nt - 1] * kBN > block_diag) --nt;
-    }
     const uint64_t* words = SCHED ? a.sched.bitmaps : a.bitmaps;
     constexpr int NLOAD = (D / 8) / NW;                      // load instructions per wavefront and operand
     constexpr int RPI = 64 / (D / 8);                        // tile rows per load instruction
     const int g_row = lane / (D / 8);                        // this lane's row inside a load instruction
 
-    // first key of tile i of this block row (>= 0), or -1 for a gathered entry
-    auto tile_start = [&](int i) -> int {
-        return SCHED ? a.sched.start[t_begin + i] : a.col_idx[t_begin + i] * kBN;
+    // The first key of every tile of the block row (>= 0, or -1 for a gathered entry) is kept in
+    // registers, one tile per lane and 128 tiles at a time, and handed out with v_readlane: a
+    // memory load of a start inside the loop would have to be waited for, and that wait would
+    // also cover the tile loads issued just before it.
+    const int32_t* starts_mem = SCHED ? a.sched.start : a.col_idx;
+    const int nt_stored = nt;
+    auto load_starts = [&](int base) -> int {
+        int v = 0x7fffffff;
+        if (base + lane < nt_stored) {
+            v = starts_mem[t_begin + base + lane];
+            if (!SCHED) v *= kBN;
+        }
+        return v;
+    };
+    int starts_lo = load_starts(0), starts_hi = load_starts(64);
+    int starts_base = 0;                                     // tile held by lane 0 of starts_lo
+    if (!SCHED && a.causal) {                                // drop tiles that are entirely in the future
+        const long long block_diag = (long long)qb * BM + (BM - 1) + off;
+        int visible = 0;                                     // columns ascend: the visible tiles come first
+        for (int base = 0; base < nt_stored; base += 64) {
+            const int v = base == 0 ? starts_lo : (base == 64 ? starts_hi : load_starts(base));
+            visible += __popcll(__ballot((long long)v <= block_diag));
+        }
+        nt = visible;
+    }
+    auto tile_start = [&](int i) -> int {                    // i is uniform, starts_base <= i
+        if (i - starts_base >= 128) {                        // once per 64 tiles beyond the first 128
+            starts_lo = starts_hi;
+            starts_base += 64;
+            starts_hi = load_starts(starts_base + 64);
+            asm volatile("" : "+v"(starts_hi));              // take the load's wait here, not in every iteration
+        }
+        const int rel = i - starts_base;
+        return rel < 64 ? __builtin_amdgcn_readlane(starts_lo, rel)
+                        : __builtin_amdgcn_readlane(starts_hi, rel - 64);
     };
     // keys of the rows this lane loads, for a gathered entry
     auto load_gather_idx = [&](int i, int* gidx) {
@@ -246,11 +296,15 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
         const int stage = (STAGES == 2) ? (it & 1) : 0;
         lds_u16* Ks = lds + stage * 2 * TILE;
         lds_u16* Vs = Ks + TILE;
-        uint64_t word = word_next;
         const int k0 = k0_next;
 
         wait_vmem();                                         // my loads of this tile have landed
         __syncthreads();                                     // ... and everybody else's
+        // The word was loaded one iteration ago.  Taking it over here, through an opaque copy,
+        // keeps the register of the pending load itself loop-carried: a compiler-made copy at the
+        // loop end would have to wait for that load, and with it for the tile loads in flight.
+        uint64_t word = word_next;
+        asm volatile("" : "+v"(word));
         if (STAGES == 2 && it + 1 < nt) {
             k0_next = start_ahead;
             issue_tile(k0_next, gidx, lds + (stage ^ 1) * 2 * TILE);
@@ -274,14 +328,23 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+            {
+                // all key operands of the tile are requested from LDS first, so that the matrix
+                // instructions wait for LDS latency once, not once per pair
+                bf16x8 kreg[KSTEPS][2];
 #pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) {
+                for (int kk = 0; kk < KSTEPS; ++kk)
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const bf16x8 kreg = *reinterpret_cast<const bf16x8*>(
-                        (const uint16_t*)Ks + (kb * 32 + n) * D + ((2 * kk) ^ k_swz) * 8);
-                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg, qreg[kk], sacc[kb], 0, 0, 0);
-                }
+                    for (int kb = 0; kb < 2; ++kb)
+                        kreg[kk][kb] = *reinterpret_cast<const bf16x8*>(
+                            (const uint16_t*)Ks + (kb * 32 + n) * D + ((2 * kk) ^ k_swz) * 8);
+#pragma unroll
+                for (int kk = 0; kk < KSTEPS; ++kk)
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+                        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk][kb], qreg[kk], sacc[kb], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * KSTEPS, 0);   // LDS reads ...
+                __builtin_amdgcn_sched_group_barrier(0x008, 2 * KSTEPS, 0);   // ... then matrix ops
             }
 
             // ---- mask in registers, row maximum
@@ -329,21 +392,31 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
                     for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
             }
 
-            // ---- O^T += V^T P^T
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                bf16x8 pb;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[ks >> 1][8 * (ks & 1) + e];
+            // ---- O^T += V^T P^T : the value operands of 16-key step ks + 1 are requested from
+            // LDS before the matrix instructions of step ks are issued
+            auto read_v = [&](int ks, bf16x8* vreg) {
 #pragma unroll
                 for (int db = 0; db < DBLK; ++db) {
                     const int chunk = ((db ^ v_swz) << 2) + v_chunk_lo;
                     lds_u16* p0 = Vs + (16 * ks + v_lane_row) * D + chunk * 8 + v_in_chunk;
                     const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p0);
                     const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * D));
-                    const bf16x8 vreg = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg, pb, oacc[db], 0, 0, 0);
+                    vreg[db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 }
+            };
+            bf16x8 vcur[DBLK], vnext[DBLK];
+            read_v(0, vcur);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                bf16x8 pb;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[ks >> 1][8 * (ks & 1) + e];
+                if (ks + 1 < 4) read_v(ks + 1, vnext);
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db)
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vcur[db], pb, oacc[db], 0, 0, 0);
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db) vcur[db] = vnext[db];
             }
         }
 
