@@ -49,6 +49,7 @@ typedef __attribute__((address_space(3))) uint16_t lds_u16;
 constexpr int kBN = 64;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLazy = 8.0f;   // log2 of the largest P before the softmax reference is raised
 
 // Swizzles: the 16-byte chunk c of LDS row r is stored at chunk position c ^ f(r).
 // Key rows are read as one chunk per lane by 32 consecutive rows; value rows are read by the
@@ -369,12 +370,23 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
             }
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
 
-            // ---- online softmax
-            const float m_new = fmaxf(m, tmax);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f((m - m_use) * sc);
-            const float msc = m_use * sc;
-            m = m_new;
+            // ---- online softmax with a lazily updated reference.  m is the reference the
+            // exponentials are taken against; it only moves up when this tile's row maximum
+            // exceeds it by more than kLazy in the log2 domain, so P stays below 2^kLazy (harmless
+            // in bf16/fp32) and the rescaling of O, 16*D/32 multiplies per lane, becomes rare.
+            // The result is the same quotient sum(p v) / sum(p) whatever reference is used.
+            const bool grow = (tmax - m) * sc > kLazy;       // m = -inf: any finite tmax grows it
+            if (__ballot(grow) != 0) {
+                // rows that keep their reference get exactly 1 (also when it still is -inf)
+                const float alpha = grow ? __builtin_amdgcn_exp2f((m - tmax) * sc) : 1.0f;   // 0 from -inf
+                m = grow ? tmax : m;
+                lsum *= alpha;
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+            }
+            const float msc = (m == -INFINITY) ? 0.f : m * sc;
             float psum = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -384,13 +396,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
                     sacc[kb][i] = p;
                     psum += p;
                 }
-            lsum = lsum * alpha + psum;
-            if (__ballot(alpha != 1.0f) != 0) {
-#pragma unroll
-                for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
-            }
+            lsum += psum;
 
             // ---- O^T += V^T P^T : the value operands of 16-key step ks + 1 are requested from
             // LDS before the matrix instructions of step ks are issued
