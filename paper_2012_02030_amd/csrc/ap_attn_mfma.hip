@@ -152,10 +152,17 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
     constexpr int CPR = D / 8;                               // 16-byte chunks per row
     constexpr int TILE = kBN * D;                            // elements of one K or V tile
     constexpr int OSTAGE = BM * D;                           // elements needed to stage O
-    constexpr int SMEM = (STAGES * 2 * TILE > OSTAGE) ? STAGES * 2 * TILE : OSTAGE;
+    constexpr int TILES = (STAGES * 2 * TILE > OSTAGE) ? STAGES * 2 * TILE : OSTAGE;
+    // per-entry metadata travels through LDS like the tiles: two slots of bitmap words (BM x 8
+    // bytes) and two slots of gather keys (64 x 4 bytes)
+    constexpr int META_W = BM * 4;                           // elements (2 bytes) of one word slot
+    constexpr int META_C = 128;                              // elements of one key slot
+    constexpr int SMEM = TILES + 2 * META_W + 2 * META_C;
 
     __shared__ __attribute__((aligned(1024))) uint16_t smem[SMEM];
     lds_u16* lds = (lds_u16*)smem;
+    lds_u16* wmeta = lds + TILES;
+    lds_u16* cmeta = wmeta + 2 * META_W;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform, and known to be
@@ -248,11 +255,29 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
         return rel < 64 ? __builtin_amdgcn_readlane(starts_lo, rel)
                         : __builtin_amdgcn_readlane(starts_hi, rel - 64);
     };
+    // Metadata of entry i of this block row, moved to LDS by wavefront 0 with the same kind of
+    // load as the tiles (so the loop holds no load that returns to registers, whose wait would
+    // also cover the tile loads in flight): its bitmap words, and its 64 gather keys.
+    const rsrc_t w_rsrc = make_rsrc(words + (size_t)t_begin * BM, (unsigned)nt_stored * BM * 8u);
+    const rsrc_t c_rsrc = make_rsrc(SCHED ? a.sched.cols + (size_t)t_begin * 64 : nullptr,
+                                    SCHED ? (unsigned)nt_stored * 256u : 0u);
+    auto dma_words = [&](int i, int slot) {
+        if (wave == 0 && lane < BM / 2)
+            load16_to_lds(lds_addr_of(wmeta + slot * META_W), lane * 16, w_rsrc, i * BM * 8);
+    };
+    auto dma_cols = [&](int i, int slot) {
+        if (wave == 0 && lane < 16)
+            load16_to_lds(lds_addr_of(cmeta + slot * META_C), lane * 16, c_rsrc, i * 256);
+    };
+    auto read_word = [&](int slot) -> uint64_t {
+        return *reinterpret_cast<const uint64_t*>(smem + TILES + slot * META_W + brow * 4);
+    };
     // keys of the rows this lane loads, for a gathered entry
-    auto load_gather_idx = [&](int i, int* gidx) {
+    auto read_cols = [&](int slot, int* gk) {
 #pragma unroll
         for (int u = 0; u < NLOAD; ++u)
-            gidx[u] = a.sched.cols[(size_t)(t_begin + i) * 64 + (wave + NW * u) * RPI + g_row];
+            gk[u] = *reinterpret_cast<const int*>(smem + TILES + 2 * META_W + slot * META_C +
+                                                  ((wave + NW * u) * RPI + g_row) * 2);
     };
     auto issue_tile = [&](int start, const int* gidx, lds_u16* Kd) {
         if (!SCHED || start >= 0) {
@@ -272,171 +297,250 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
     const int v_chunk_lo = 2 * g + ((i16 >> 1) & 1);
     const int v_swz = swz_v<D>(vj) >> 2;                     // xor on the 4-chunk group index
 
-    // first tile; the start (and gather keys) of the tile after it are fetched one step ahead
-    uint64_t word_next = 0;
-    int k0_next = 0;                                         // start of the tile whose loads were issued last
-    int start_ahead = 0;                                     // start of the tile after that
-    int gidx[NLOAD];
+    // ---- the three pieces of work on one tile, shared by both pipelines below
+
+    // S^T = K Q^T : two 32-key blocks.  Key operands are requested from LDS two groups ahead of
+    // the matrix instructions that consume them (a group = 2 contraction steps x 2 key blocks),
+    // so LDS latency is paid once per tile while only three groups are live in registers.
+    auto qk_tile = [&](lds_u16* Ks, f32x16* sacc) {
 #pragma unroll
-    for (int u = 0; u < NLOAD; ++u) gidx[u] = 0;
-    if (nt > 0) {
-        k0_next = tile_start(0);
-        if (SCHED && k0_next < 0) {
-            load_gather_idx(0, gidx);
-            wait_vmem();
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+        constexpr int GS = (KSTEPS >= 4) ? 2 : 1;            // contraction steps per group
+        constexpr int NG = KSTEPS / GS;                      // groups
+        bf16x8 kreg[KSTEPS][2];
+        auto read_group = [&](int gi) {
+#pragma unroll
+            for (int kk = gi * GS; kk < (gi + 1) * GS; ++kk)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+                    kreg[kk][kb] = *reinterpret_cast<const bf16x8*>(
+                        (const uint16_t*)Ks + (kb * 32 + n) * D + ((2 * kk) ^ k_swz) * 8);
+        };
+        auto mfma_group = [&](int gi) {
+#pragma unroll
+            for (int kk = gi * GS; kk < (gi + 1) * GS; ++kk)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+                    sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk][kb], qreg[kk], sacc[kb], 0, 0, 0);
+        };
+        read_group(0);
+        if (NG > 1) read_group(1);
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            if (gi + 2 < NG) read_group(gi + 2);
+            mfma_group(gi);
         }
-        issue_tile(k0_next, gidx, lds);
-        word_next = words[(size_t)t_begin * BM + brow];
-        if (nt > 1) {
-            start_ahead = tile_start(1);
-            if (SCHED && start_ahead < 0) load_gather_idx(1, gidx);
+        // pin that order: reads of two groups, then (reads of the next group, matrix ops of this one)
+        __builtin_amdgcn_sched_group_barrier(0x100, (NG > 1 ? 2 : 1) * 2 * GS, 0);
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) {
+            if (gi + 2 < NG) __builtin_amdgcn_sched_group_barrier(0x100, 2 * GS, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2 * GS, 0);
         }
-    }
+    };
 
-    for (int it = 0; it < nt; ++it) {
-        const int stage = (STAGES == 2) ? (it & 1) : 0;
-        lds_u16* Ks = lds + stage * 2 * TILE;
-        lds_u16* Vs = Ks + TILE;
-        const int k0 = k0_next;
+    // Mask in registers, row maximum, online softmax; leaves P in sacc.
+    auto softmax_tile = [&](uint64_t word, f32x16* sacc) {
+        float tmax = -INFINITY;
+        if (__ballot(word != ~0ull) == 0) {                  // every visible entry kept: no selects
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kb][i]);
+        } else {
+            const uint64_t wsh = word >> (4 * hh);
+            const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int pos = 8 * (i / 4) + (i % 4);
+                    const float sv = ((wbits[kb] >> pos) & 1u) ? sacc[kb][i] : -INFINITY;
+                    sacc[kb][i] = sv;
+                    tmax = fmaxf(tmax, sv);
+                }
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
 
-        wait_vmem();                                         // my loads of this tile have landed
-        __syncthreads();                                     // ... and everybody else's
-        // The word was loaded one iteration ago.  Taking it over here, through an opaque copy,
-        // keeps the register of the pending load itself loop-carried: a compiler-made copy at the
-        // loop end would have to wait for that load, and with it for the tile loads in flight.
-        uint64_t word = word_next;
-        asm volatile("" : "+v"(word));
-        if (STAGES == 2 && it + 1 < nt) {
-            k0_next = start_ahead;
-            issue_tile(k0_next, gidx, lds + (stage ^ 1) * 2 * TILE);
-            word_next = words[(size_t)(t_begin + it + 1) * BM + brow];
-            if (it + 2 < nt) {
-                start_ahead = tile_start(it + 2);
-                if (SCHED && start_ahead < 0) load_gather_idx(it + 2, gidx);
+        // Online softmax with a lazily updated reference.  m is the reference the exponentials
+        // are taken against; it only moves up when this tile's row maximum exceeds it by more
+        // than kLazy in the log2 domain, so P stays below 2^kLazy (harmless in bf16/fp32) and the
+        // rescaling of O, 16*D/32 multiplies per lane, becomes rare.  The result is the same
+        // quotient sum(p v) / sum(p) whatever reference is used.
+        const bool grow = (tmax - m) * sc > kLazy;           // m = -inf: any finite tmax grows it
+        if (__ballot(grow) != 0) {
+            // rows that keep their reference get exactly 1 (also when it still is -inf)
+            const float alpha = grow ? __builtin_amdgcn_exp2f((m - tmax) * sc) : 1.0f;   // 0 from -inf
+            m = grow ? tmax : m;
+            lsum *= alpha;
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+        }
+        const float msc = (m == -INFINITY) ? 0.f : m * sc;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float pe = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -msc));
+                sacc[kb][i] = pe;
+                psum += pe;
             }
-        }
+        lsum += psum;
+    };
 
+    // O^T += V^T P^T : the value operands of 16-key step ks + 1 are requested from LDS before the
+    // matrix instructions of step ks are issued.
+    auto pv_tile = [&](lds_u16* Vs, const f32x16* sacc) {
+        auto read_v = [&](int ks, bf16x8* vreg) {
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db) {
+                const int chunk = ((db ^ v_swz) << 2) + v_chunk_lo;
+                lds_u16* p0 = Vs + (16 * ks + v_lane_row) * D + chunk * 8 + v_in_chunk;
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p0);
+                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * D));
+                vreg[db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+        };
+        bf16x8 vcur[DBLK], vnext[DBLK];
+        read_v(0, vcur);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 pb;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[ks >> 1][8 * (ks & 1) + e];
+            if (ks + 1 < 4) read_v(ks + 1, vnext);
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vcur[db], pb, oacc[db], 0, 0, 0);
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db) vcur[db] = vnext[db];
+        }
+    };
+
+    auto apply_causal = [&](uint64_t word, int k0) -> uint64_t {
         if (!SCHED && a.causal) {
             const long long lim = diag - k0;
             if (lim < 0) word = 0;
             else if (lim < 63) word &= (2ull << lim) - 1ull;
         }
+        return word;
+    };
 
-        if (__ballot(word != 0) != 0) {                      // something visible for these 32 queries
-            // ---- S^T = K Q^T : two 32-key blocks
-            f32x16 sacc[2];
+    int gidx[NLOAD];                                         // gather keys of the next tile to be issued
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+    for (int u = 0; u < NLOAD; ++u) gidx[u] = 0;
+    // First use of the Q registers, placed before the loops: the wait that the compiler attaches
+    // to the first use of a loaded register would otherwise sit inside the loop, in front of the
+    // first matrix instruction, and there it would also wait for the tile loads just issued.
+    auto settle_q = [&]() {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
-            {
-                // all key operands of the tile are requested from LDS first, so that the matrix
-                // instructions wait for LDS latency once, not once per pair
-                bf16x8 kreg[KSTEPS][2];
-#pragma unroll
-                for (int kk = 0; kk < KSTEPS; ++kk)
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-                        kreg[kk][kb] = *reinterpret_cast<const bf16x8*>(
-                            (const uint16_t*)Ks + (kb * 32 + n) * D + ((2 * kk) ^ k_swz) * 8);
-#pragma unroll
-                for (int kk = 0; kk < KSTEPS; ++kk)
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-                        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk][kb], qreg[kk], sacc[kb], 0, 0, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2 * KSTEPS, 0);   // LDS reads ...
-                __builtin_amdgcn_sched_group_barrier(0x008, 2 * KSTEPS, 0);   // ... then matrix ops
+        for (int kk = 0; kk < KSTEPS; ++kk) asm volatile("" : "+v"(qreg[kk]));
+    };
+
+    if constexpr (STAGES == 2) {
+        // ---- Pipeline A: two LDS stages of (K, V); the whole next tile is in flight while the
+        // current one is computed; one barrier per tile.
+        int k0_next = 0;                                     // start of the tile whose loads were issued last
+        if (nt > 0) {
+            k0_next = tile_start(0);
+            if (SCHED && k0_next < 0) {                      // the very first entry is gathered: fetch its keys
+                dma_cols(0, 0);
+                wait_vmem();
+                __syncthreads();
+                read_cols(0, gidx);
             }
+            issue_tile(k0_next, gidx, lds);
+            dma_words(0, 0);
+            if (SCHED && nt > 1 && tile_start(1) < 0) dma_cols(1, 1);
+        }
+        settle_q();
+        for (int it = 0; it < nt; ++it) {
+            const int stage = it & 1;
+            lds_u16* Ks = lds + stage * 2 * TILE;
+            lds_u16* Vs = Ks + TILE;
+            const int k0 = k0_next;
 
-            // ---- mask in registers, row maximum
-            float tmax = -INFINITY;
-            if (__ballot(word != ~0ull) == 0) {              // every visible entry kept: no selects
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kb][i]);
-            } else {
-                const uint64_t wsh = word >> (4 * hh);
-                const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int pos = 8 * (i / 4) + (i % 4);
-                        const float s = ((wbits[kb] >> pos) & 1u) ? sacc[kb][i] : -INFINITY;
-                        sacc[kb][i] = s;
-                        tmax = fmaxf(tmax, s);
-                    }
+            wait_vmem();                                     // my loads of this tile have landed
+            __syncthreads();                                 // ... and everybody else's
+            uint64_t word = read_word(stage);
+            if (it + 1 < nt) {
+                k0_next = tile_start(it + 1);
+                if (SCHED && k0_next < 0) read_cols(stage ^ 1, gidx);
+                issue_tile(k0_next, gidx, lds + (stage ^ 1) * 2 * TILE);
+                dma_words(it + 1, stage ^ 1);
+                if (SCHED && it + 2 < nt && tile_start(it + 2) < 0) dma_cols(it + 2, stage);
             }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-
-            // ---- online softmax with a lazily updated reference.  m is the reference the
-            // exponentials are taken against; it only moves up when this tile's row maximum
-            // exceeds it by more than kLazy in the log2 domain, so P stays below 2^kLazy (harmless
-            // in bf16/fp32) and the rescaling of O, 16*D/32 multiplies per lane, becomes rare.
-            // The result is the same quotient sum(p v) / sum(p) whatever reference is used.
-            const bool grow = (tmax - m) * sc > kLazy;       // m = -inf: any finite tmax grows it
-            if (__ballot(grow) != 0) {
-                // rows that keep their reference get exactly 1 (also when it still is -inf)
-                const float alpha = grow ? __builtin_amdgcn_exp2f((m - tmax) * sc) : 1.0f;   // 0 from -inf
-                m = grow ? tmax : m;
-                lsum *= alpha;
-#pragma unroll
-                for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
-            }
-            const float msc = (m == -INFINITY) ? 0.f : m * sc;
-            float psum = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -msc));
-                    sacc[kb][i] = p;
-                    psum += p;
-                }
-            lsum += psum;
-
-            // ---- O^T += V^T P^T : the value operands of 16-key step ks + 1 are requested from
-            // LDS before the matrix instructions of step ks are issued
-            auto read_v = [&](int ks, bf16x8* vreg) {
-#pragma unroll
-                for (int db = 0; db < DBLK; ++db) {
-                    const int chunk = ((db ^ v_swz) << 2) + v_chunk_lo;
-                    lds_u16* p0 = Vs + (16 * ks + v_lane_row) * D + chunk * 8 + v_in_chunk;
-                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p0);
-                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * D));
-                    vreg[db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-            };
-            bf16x8 vcur[DBLK], vnext[DBLK];
-            read_v(0, vcur);
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                bf16x8 pb;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pb[e] = (__bf16)sacc[ks >> 1][8 * (ks & 1) + e];
-                if (ks + 1 < 4) read_v(ks + 1, vnext);
-#pragma unroll
-                for (int db = 0; db < DBLK; ++db)
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vcur[db], pb, oacc[db], 0, 0, 0);
-#pragma unroll
-                for (int db = 0; db < DBLK; ++db) vcur[db] = vnext[db];
+            word = apply_causal(word, k0);
+            if (__ballot(word != 0) != 0) {                  // something visible for these 32 queries
+                f32x16 sacc[2];
+                qk_tile(Ks, sacc);
+                softmax_tile(word, sacc);
+                pv_tile(Vs, sacc);
             }
         }
-
-        if (STAGES == 1) {
-            __syncthreads();                                 // the single stage is free again
+    } else {
+        // ---- Pipeline B: one K buffer and one V buffer (half the LDS, twice the workgroups per
+        // CU).  K of the next tile and V of the current tile are loaded while the current
+        // tile's softmax runs: K is free once every wavefront has its scores, V once every
+        // wavefront is past the previous tile's second product.  Two barriers per tile.
+        lds_u16* Ks = lds;
+        lds_u16* Vs = lds + TILE;
+        int gcur[NLOAD];                                     // gather keys of the current tile (for its V)
+#pragma unroll
+        for (int u = 0; u < NLOAD; ++u) gcur[u] = 0;
+        int s_cur = 0, s_nxt = 0;                            // starts of tile it and tile it + 1
+        if (nt > 0) {
+            s_cur = tile_start(0);
+            if (SCHED && s_cur < 0) {                        // the very first entry is gathered: fetch its keys
+                dma_cols(0, 0);
+                wait_vmem();
+                __syncthreads();
+                read_cols(0, gcur);
+            }
+            if (!SCHED || s_cur >= 0) issue_tile_loads<D, NW, false>(k_rsrc, Ks, s_cur, sk_bytes, wave, lane);
+            else issue_gather_loads<D, NW, false>(k_rsrc, Ks, gcur, sk_bytes, wave, lane);
+            dma_words(0, 0);
+            if (nt > 1) {
+                s_nxt = tile_start(1);
+                if (SCHED && s_nxt < 0) dma_cols(1, 1);
+            }
+            wait_vmem();
+            __syncthreads();
+        }
+        settle_q();
+        for (int it = 0; it < nt; ++it) {
+            const int slot = it & 1;
+            const uint64_t word = apply_causal(read_word(slot), s_cur);
+            const bool active = __ballot(word != 0) != 0;    // something visible for these 32 queries
+            f32x16 sacc[2];
+            if (active) qk_tile(Ks, sacc);
+            if (SCHED && it + 1 < nt && s_nxt < 0) read_cols(slot ^ 1, gidx);
+            __syncthreads();                                 // K buffer and V buffer are free
             if (it + 1 < nt) {
-                k0_next = start_ahead;
-                issue_tile(k0_next, gidx, lds);
-                word_next = words[(size_t)(t_begin + it + 1) * BM + brow];
+                if (!SCHED || s_nxt >= 0) issue_tile_loads<D, NW, false>(k_rsrc, Ks, s_nxt, sk_bytes, wave, lane);
+                else issue_gather_loads<D, NW, false>(k_rsrc, Ks, gidx, sk_bytes, wave, lane);
+            }
+            if (!SCHED || s_cur >= 0) issue_tile_loads<D, NW, true>(v_rsrc, Vs, s_cur, sv_bytes, wave, lane);
+            else issue_gather_loads<D, NW, true>(v_rsrc, Vs, gcur, sv_bytes, wave, lane);
+            if (it + 1 < nt) {
+                dma_words(it + 1, slot ^ 1);
+                s_cur = s_nxt;
+#pragma unroll
+                for (int u = 0; u < NLOAD; ++u) gcur[u] = gidx[u];
                 if (it + 2 < nt) {
-                    start_ahead = tile_start(it + 2);
-                    if (SCHED && start_ahead < 0) load_gather_idx(it + 2, gidx);
+                    s_nxt = tile_start(it + 2);
+                    if (SCHED && s_nxt < 0) dma_cols(it + 2, slot);
                 }
             }
+            if (active) softmax_tile(word, sacc);
+            wait_vmem();                                     // V of this tile, K of the next, their metadata
+            __syncthreads();
+            if (active) pv_tile(Vs, sacc);
         }
     }
 

@@ -56,38 +56,45 @@ __global__ __launch_bounds__(128) void build_schedule_kernel(
     int fill = 0;                                          // columns in the open gathered entry
     size_t tail_slot = 0;                                  // its slot, reserved when its first column arrives
 
-    for (int t = t0; t < t1; ++t) {
-        const int k0 = col_idx[t] * 64;
-        uint64_t word = bitmaps[(size_t)t * BM + row];
-        if (causal) {
-            const long long lim = diag - k0;
-            if (lim < 0) word = 0;
-            else if (lim < 63) word &= (2ull << lim) - 1ull;
-        }
-        uint64_t colmask = block_or(word, red);
-        const int ncols = __popcll(colmask);
-        if (ncols == 0) continue;                          // nothing visible
-        if (ncols >= min_cols) {                           // keep as a tile of 64 consecutive keys
-            const size_t e = (size_t)t0 + n_out;
-            if (row == 0) s.start[e] = k0;
-            s.bitmaps[e * BM + row] = word;
-            ++n_out;
-            continue;
-        }
-        while (colmask) {                                  // append the visible columns, ascending
-            const int bit = __ffsll((long long)colmask) - 1;
-            colmask &= colmask - 1;
-            if (fill == 0) {                               // open a gathered entry: one per <= 64 columns,
-                tail_slot = (size_t)t0 + n_out;            // so never more entries than tiles seen so far
-                ++n_out;
-                if (row == 0) s.start[tail_slot] = -1;
+    // Two passes over the stored tiles: first the entries that stay runs of 64 consecutive keys,
+    // then the gathered ones, so that the attention kernel meets a gathered entry (whose keys it
+    // must fetch before it can load anything) only after it has other loads in flight.
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int t = t0; t < t1; ++t) {
+            const int k0 = col_idx[t] * 64;
+            uint64_t word = bitmaps[(size_t)t * BM + row];
+            if (causal) {
+                const long long lim = diag - k0;
+                if (lim < 0) word = 0;
+                else if (lim < 63) word &= (2ull << lim) - 1ull;
             }
-            tail_word |= ((word >> bit) & 1ull) << fill;
-            if (row == 0) s.cols[tail_slot * 64 + fill] = k0 + bit;
-            if (++fill == 64) {
-                s.bitmaps[tail_slot * BM + row] = tail_word;
-                tail_word = 0;
-                fill = 0;
+            uint64_t colmask = block_or(word, red);
+            const int ncols = __popcll(colmask);
+            if (ncols == 0) continue;                      // nothing visible
+            const bool consecutive = ncols >= min_cols;
+            if (consecutive != (pass == 0)) continue;
+            if (consecutive) {                             // keep as a tile of 64 consecutive keys
+                const size_t e = (size_t)t0 + n_out;
+                if (row == 0) s.start[e] = k0;
+                s.bitmaps[e * BM + row] = word;
+                ++n_out;
+                continue;
+            }
+            while (colmask) {                              // append the visible columns, ascending
+                const int bit = __ffsll((long long)colmask) - 1;
+                colmask &= colmask - 1;
+                if (fill == 0) {                           // open a gathered entry: one per <= 64 columns,
+                    tail_slot = (size_t)t0 + n_out;        // so never more entries than visible tiles
+                    ++n_out;
+                    if (row == 0) s.start[tail_slot] = -1;
+                }
+                tail_word |= ((word >> bit) & 1ull) << fill;
+                if (row == 0) s.cols[tail_slot * 64 + fill] = k0 + bit;
+                if (++fill == 64) {
+                    s.bitmaps[tail_slot * BM + row] = tail_word;
+                    tail_word = 0;
+                    fill = 0;
+                }
             }
         }
     }
