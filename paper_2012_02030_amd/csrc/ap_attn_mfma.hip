@@ -362,7 +362,10 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
                     tmax = fmaxf(tmax, sv);
                 }
         }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        {   // the other half of this query's keys lives in lane ^ 32: one swap of the wave halves
+            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+            tmax = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+        }
 
         // Online softmax with a lazily updated reference.  m is the reference the exponentials
         // are taken against; it only moves up when this tile's row maximum exceeds it by more
@@ -545,7 +548,11 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
     }
 
     // ---- epilogue: normalise, stage O through LDS, coalesced stores; lse
-    const float ltot = lsum + __shfl_xor(lsum, 32, 64);
+    float ltot;                                              // both halves of the row sum
+    {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
+        ltot = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
     const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
     __syncthreads();                                         // all wavefronts are done with K/V in LDS
     uint16_t* ostage = smem + wave * 32 * D;                 // this wavefront's 32 rows
