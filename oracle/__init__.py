@@ -13,6 +13,9 @@ build_layout       block-sparse layout (block rows, block columns, per-block ele
                    of an element mask; Section 9.2 uses block-structured sparseness patterns
 macs_fraction      Appendix A's multiply-accumulate count, the model behind Eq. (3)
 kept_entry_flops   4*D flops per kept (query, key) connection: both N^2-sized products
+
+Mask construction (Section 3.2, Eq. (1) and Eq. (2)) is in ``mask_construction.py`` (numpy):
+attention_maps, mean_attention_map, percentile_threshold, prune_mask.
 """
 from __future__ import annotations
 
@@ -21,6 +24,9 @@ import os
 import subprocess
 
 import numpy as np
+
+from .mask_construction import (attention_maps, mean_attention_map,  # noqa: F401
+                                percentile_threshold, prune_mask)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ap_oracle.c")
