@@ -172,6 +172,68 @@ ap_status ap_sparse_attn_fwd(const void *Q, const void *K, const void *V, void *
                              const ap_schedule *sched, int causal, float softmax_scale,
                              void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Mask construction, step 1: accumulate attention matrices into the mean map (Section 3.2,
+ * Eq. (1)).
+ *
+ * For every head h, query i and key j (if `causal`, only j <= i + (Lk - Lq)):
+ *
+ *     abar[h,i,j] += weight * sum_b  exp(s_bij) / sum_j' exp(s_bij'),   s_bij = scale * <Q[b,h,i,:], K[b,h,j,:]>
+ *
+ * i.e. the attention matrices A_b = softmax(Q_b K_b^T / sqrt(d_k)) of the B examples of this call
+ * (Section 3.2: the masked-attention equation with the zero mask), summed element-wise.  Zero
+ * `abar`, then call once per batch of the data set with weight = 1/n (n = number of examples
+ * in the whole set) to obtain Eq. (1)'s mean; the running sum is kept in fp32.  Entries that
+ * causality hides are neither read nor written.
+ *
+ *   Q [B, H, Lq, D], K [B, H, Lk, D]   as in ap_sparse_attn_fwd (bf16 only)
+ *   abar          in/out, float [H, Lq, Lk] contiguous
+ *   workspace     device scratch of at least ap_attention_maps_workspace_bytes(B, H, Lq) bytes
+ *                 (the row-wise log-sum-exp of the scores), 16-byte aligned; contents undefined
+ *                 before and after
+ *
+ * Supported: dtype = AP_BF16, D in {32, 64, 128}.  Two launches on `stream`.  Deterministic.
+ * ------------------------------------------------------------------------------------------- */
+size_t ap_attention_maps_workspace_bytes(int B, int H, int Lq);
+
+ap_status ap_accumulate_attention_maps(const void *Q, const void *K, ap_dtype dtype, int B, int H,
+                                       int Lq, int Lk, int D, const int64_t *stride_q,
+                                       const int64_t *stride_k, int causal, float softmax_scale,
+                                       float weight, float *abar, void *workspace,
+                                       size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Mask construction, step 2: layer-wise percentile threshold and pruning mask (Section 3.2,
+ * paragraph before Eq. (2), and Eq. (2)).
+ *
+ * `abar` holds the mean maps of ALL heads of one attention layer.  With its N participating
+ * entries (all H*Lq*Lk of them, or, if `causal`, those with j <= i + (Lk - Lq)) in ascending
+ * order v[0] <= ... <= v[N-1], the threshold is the order statistic
+ *
+ *     tau = v[ floor(prune_fraction * N) ]          (no interpolation; +infinity if the rank is N)
+ *
+ * and an entry is pruned iff abar[h,i,j] < tau (strict: ties with tau are kept), so that with
+ * distinct values exactly floor(prune_fraction * N) entries are pruned.  Output is the keep
+ * mask that ap_build_layout consumes: mask[h,i,j] = 1 if participating and abar[h,i,j] >= tau,
+ * else 0.  The rank is computed in double precision on the host exactly as written above.
+ *
+ *   abar          float [H, Lq, Lk] contiguous, 16-byte aligned; values must be >= 0 and not
+ *                 NaN (they are means of probabilities)
+ *   prune_fraction  p of the paper as a fraction, 0 <= p <= 1
+ *   mask          out, uint8 [H, Lq, Lk] contiguous
+ *   tau_out       out, one float (device), or NULL
+ *   workspace     device scratch of at least ap_prune_mask_workspace_bytes() bytes, 16-byte
+ *                 aligned; contents undefined before and after
+ *
+ * Exact: tau is an element of abar, found by a three-pass radix selection over the bit
+ * patterns; integer atomics only, so the result is bit-identical from run to run.
+ * ------------------------------------------------------------------------------------------- */
+size_t ap_prune_mask_workspace_bytes(void);
+
+ap_status ap_prune_mask(const float *abar, int H, int Lq, int Lk, int causal, double prune_fraction,
+                        uint8_t *mask, float *tau_out, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
 #ifdef __cplusplus
 }
 #endif

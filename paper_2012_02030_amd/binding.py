@@ -25,7 +25,9 @@ AP_F32 = 0
 AP_BF16 = 1
 
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
-           "ap_build_layout", "ap_build_schedule", "ap_sparse_attn_fwd")
+           "ap_build_layout", "ap_build_schedule", "ap_sparse_attn_fwd",
+           "ap_attention_maps_workspace_bytes", "ap_accumulate_attention_maps",
+           "ap_prune_mask_workspace_bytes", "ap_prune_mask")
 
 
 class _CSchedule(ctypes.Structure):
@@ -71,6 +73,18 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(i64), ctypes.POINTER(i64),
                                          vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
                                          ctypes.c_float, vp]
+        L.ap_attention_maps_workspace_bytes.restype = ctypes.c_size_t
+        L.ap_attention_maps_workspace_bytes.argtypes = [i32] * 3
+        L.ap_accumulate_attention_maps.restype = i32
+        L.ap_accumulate_attention_maps.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32,
+                                                   ctypes.POINTER(i64), ctypes.POINTER(i64), i32,
+                                                   ctypes.c_float, ctypes.c_float, vp, vp,
+                                                   ctypes.c_size_t, vp]
+        L.ap_prune_mask_workspace_bytes.restype = ctypes.c_size_t
+        L.ap_prune_mask_workspace_bytes.argtypes = []
+        L.ap_prune_mask.restype = i32
+        L.ap_prune_mask.argtypes = [vp, i32, i32, i32, i32, ctypes.c_double, vp, vp, vp,
+                                    ctypes.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -229,3 +243,63 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_fwd")
     return out, lse
+
+
+def ap_attention_maps_workspace_bytes(B: int, H: int, Lq: int) -> int:
+    return int(lib().ap_attention_maps_workspace_bytes(B, H, Lq))
+
+
+def ap_accumulate_attention_maps(Q: torch.Tensor, K: torch.Tensor,
+                                 abar: Optional[torch.Tensor] = None, causal: bool = False,
+                                 softmax_scale: float = 0.0, weight: float = 1.0,
+                                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """abar [H,Lq,Lk] fp32 += weight * sum_b softmax(Q_b K_b^T * scale); a new zeroed abar when
+    none is given.  Q [B,H,Lq,D], K [B,H,Lk,D] bf16 device tensors.  Asynchronous on the stream."""
+    if Q.dtype != torch.bfloat16 or K.dtype != torch.bfloat16:
+        raise ValueError("Q and K must be bfloat16")
+    if Q.dim() != 4 or K.dim() != 4:
+        raise ValueError("Q, K must be [B, H, L, D]")
+    B, H, Lq, D = Q.shape
+    Lk = K.shape[2]
+    if tuple(K.shape) != (B, H, Lk, D):
+        raise ValueError("K shape mismatch")
+    if Q.stride(3) != 1 or K.stride(3) != 1:
+        raise ValueError("last dimension must be contiguous")
+    if abar is None:
+        abar = torch.zeros((H, Lq, Lk), dtype=torch.float32, device=Q.device)
+    if abar.dtype != torch.float32 or tuple(abar.shape) != (H, Lq, Lk) or not abar.is_contiguous():
+        raise ValueError("abar must be a contiguous float32 tensor [H, Lq, Lk]")
+    ws_bytes = ap_attention_maps_workspace_bytes(B, H, Lq)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=Q.device)
+    st = lib().ap_accumulate_attention_maps(
+        Q.data_ptr(), K.data_ptr(), AP_BF16, B, H, Lq, Lk, D, _strides3(Q), _strides3(K),
+        int(bool(causal)), float(softmax_scale), float(weight), abar.data_ptr(), ws.data_ptr(),
+        ws_bytes, _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_accumulate_attention_maps")
+    return abar
+
+
+def ap_prune_mask_workspace_bytes() -> int:
+    return int(lib().ap_prune_mask_workspace_bytes())
+
+
+def ap_prune_mask(abar: torch.Tensor, prune_fraction: float, causal: bool = False,
+                  stream: Optional[torch.cuda.Stream] = None):
+    """abar: float32 device tensor [H, Lq, Lk], the mean maps of all heads of one layer.
+
+    Returns (mask uint8 [H,Lq,Lk] with 1 = kept, tau float32 [1] on device).  Asynchronous."""
+    if abar.dtype != torch.float32 or abar.dim() != 3 or not abar.is_cuda:
+        raise ValueError("abar must be a float32 device tensor [H, Lq, Lk]")
+    abar = abar.contiguous()
+    H, Lq, Lk = abar.shape
+    mask = torch.empty((H, Lq, Lk), dtype=torch.uint8, device=abar.device)
+    tau = torch.empty(1, dtype=torch.float32, device=abar.device)
+    ws_bytes = ap_prune_mask_workspace_bytes()
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=abar.device)
+    st = lib().ap_prune_mask(abar.data_ptr(), H, Lq, Lk, int(bool(causal)), float(prune_fraction),
+                             mask.data_ptr(), tau.data_ptr(), ws.data_ptr(), ws_bytes,
+                             _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_prune_mask")
+    return mask, tau

@@ -156,4 +156,77 @@ ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* 
     return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
+size_t ap_attention_maps_workspace_bytes(int B, int H, int Lq)
+{
+    if (B <= 0 || H <= 0 || Lq <= 0) return 0;
+    return (size_t)B * (size_t)H * (size_t)Lq * sizeof(float);
+}
+
+ap_status ap_accumulate_attention_maps(const void* Q, const void* K, ap_dtype dtype, int B, int H,
+                                       int Lq, int Lk, int D, const int64_t* stride_q,
+                                       const int64_t* stride_k, int causal, float softmax_scale,
+                                       float weight, float* abar, void* workspace,
+                                       size_t workspace_bytes, void* stream)
+{
+    if (!Q || !K || !stride_q || !stride_k || !abar || !workspace) return AP_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || Lq <= 0 || Lk <= 0 || D <= 0) return AP_ERR_INVALID_ARG;
+    if (dtype != AP_F32 && dtype != AP_BF16) return AP_ERR_INVALID_ARG;
+    if (causal && Lk < Lq) return AP_ERR_INVALID_ARG;
+    if (isnan(softmax_scale) || isinf(softmax_scale) || isnan(weight) || isinf(weight))
+        return AP_ERR_INVALID_ARG;
+    if (dtype != AP_BF16) return AP_ERR_UNSUPPORTED;
+    if (!(D == 32 || D == 64 || D == 128)) return AP_ERR_UNSUPPORTED;
+    const long long nQB = (Lq + 63) / 64, nKB = (Lk + 63) / 64;
+    if (nQB * H * B >= 2147483647LL || nQB * nKB * H >= 2147483647LL) return AP_ERR_UNSUPPORTED;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(abar, 16) || !aligned(workspace, 16))
+        return AP_ERR_INVALID_ARG;
+    if (!strides_ok(stride_q, D, 8) || !strides_ok(stride_k, D, 8)) return AP_ERR_INVALID_ARG;
+    if ((long long)Lk * stride_k[2] * 2 >= 2147483647LL) return AP_ERR_UNSUPPORTED;
+    if (workspace_bytes < ap_attention_maps_workspace_bytes(B, H, Lq)) return AP_ERR_CAPACITY;
+
+    ap::MapArgs a;
+    a.Q = Q; a.K = K;
+    a.B = B; a.H = H; a.Lq = Lq; a.Lk = Lk; a.D = D;
+    for (int k = 0; k < 3; ++k) { a.sq[k] = stride_q[k]; a.sk[k] = stride_k[k]; }
+    a.causal = causal ? 1 : 0;
+    a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+    a.weight = weight;
+    a.abar = abar;
+    a.lse2 = (float*)workspace;
+    return ap::launch_attention_maps(a, (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+size_t ap_prune_mask_workspace_bytes(void) { return ap::prune_mask_workspace_bytes(); }
+
+ap_status ap_prune_mask(const float* abar, int H, int Lq, int Lk, int causal, double prune_fraction,
+                        uint8_t* mask, float* tau_out, void* workspace, size_t workspace_bytes,
+                        void* stream)
+{
+    if (!abar || !mask || !workspace) return AP_ERR_INVALID_ARG;
+    if (H <= 0 || Lq <= 0 || Lk <= 0) return AP_ERR_INVALID_ARG;
+    if (!(prune_fraction >= 0.0 && prune_fraction <= 1.0)) return AP_ERR_INVALID_ARG;   // also NaN
+    if (causal && Lk < Lq) return AP_ERR_INVALID_ARG;
+    if ((long long)H * Lq >= 2147483647LL) return AP_ERR_UNSUPPORTED;
+    if (!aligned(abar, 16) || !aligned(mask, 4) || !aligned(tau_out, 4) || !aligned(workspace, 16))
+        return AP_ERR_INVALID_ARG;
+    if (workspace_bytes < ap::prune_mask_workspace_bytes()) return AP_ERR_CAPACITY;
+
+    // participating entries: every row's visible prefix
+    unsigned long long N;
+    if (causal) {
+        // row i sees min(Lk, i + Lk - Lq + 1) = i + (Lk - Lq) + 1 keys (Lk >= Lq)
+        const unsigned long long per_head =
+            (unsigned long long)Lq * (unsigned long long)(Lk - Lq) +
+            (unsigned long long)Lq * ((unsigned long long)Lq + 1ull) / 2ull;
+        N = per_head * (unsigned long long)H;
+    } else {
+        N = (unsigned long long)H * (unsigned long long)Lq * (unsigned long long)Lk;
+    }
+    const double want = floor(prune_fraction * (double)N);
+    const bool none = want >= (double)N;
+    const unsigned long long rank = none ? 0ull : (unsigned long long)want;
+    return ap::launch_prune_mask(abar, H, Lq, Lk, causal ? 1 : 0, rank, none, mask, tau_out, workspace,
+                                 (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
 }  // extern "C"

@@ -50,4 +50,25 @@ hipError_t launch_fwd_valu(const FwdArgs& a, bool bf16, hipStream_t stream);
 // bf16 matrix-core kernel; block_m 64 or 128, block_n 64
 hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream);
 
+// ---- mask construction: mean attention map (ap_maps.hip)
+struct MapArgs {
+    const void* Q;
+    const void* K;
+    int B, H, Lq, Lk, D;
+    long long sq[3], sk[3];         // element strides: batch, head, sequence
+    int causal;
+    float scale;                    // already resolved (> 0)
+    float weight;
+    float* abar;                    // [H, Lq, Lk], accumulated into
+    float* lse2;                    // [B, H, Lq] scratch: base-2 log-sum-exp of each score row
+};
+hipError_t launch_attention_maps(const MapArgs& a, hipStream_t stream);
+
+// ---- mask construction: percentile threshold and mask (ap_threshold.hip)
+size_t prune_mask_workspace_bytes();
+// rank: 0-based position of tau among the participating entries; none: prune everything
+hipError_t launch_prune_mask(const float* abar, int H, int Lq, int Lk, int causal,
+                             unsigned long long rank, bool none, uint8_t* mask, float* tau_out,
+                             void* workspace, hipStream_t stream);
+
 }  // namespace ap

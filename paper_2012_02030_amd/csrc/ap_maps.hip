@@ -1,0 +1,290 @@
+// Accumulation of attention matrices into the mean attention map (Section 3.2, Eq. (1)).
+//
+// The attention matrix of one example, A_b = softmax(Q_b K_b^T / sqrt(d_k)), is never stored:
+// it would be B*H*Lq*Lk probabilities.  Two kernels instead:
+//
+//   row_lse_kernel         one workgroup per (example, head, 64 queries): walks all key tiles,
+//                          S^T = K Q^T on the matrix cores, keeps the online row maximum and row
+//                          sum, and writes the row's log-sum-exp (base 2) to the workspace.
+//   map_accumulate_kernel  one workgroup per (head, 64 queries, 64 keys): loops over the examples,
+//                          recomputes the 64x64 scores, P = exp2(s - lse), and sums P in
+//                          registers; the running map in memory is read and written once per
+//                          call, whatever the batch size.
+//
+// Both use the score layout of the attention kernel: a wavefront owns 32 queries, lane l holds
+// query l % 32 and, of each 32-key block, the keys 8*(i/4) + 4*(l/32) + i%4 (i = 0..15).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ap_internal.h"
+#include "ap_mfma_common.h"
+
+namespace ap {
+
+namespace {
+
+using namespace mfma;
+
+// S^T of one 64-key tile held in LDS (swizzled rows of D bf16) against the Q^T operand in
+// registers; n = query inside the wavefront, k_swz = (lane / 32) ^ swz_k(n).
+template <int D>
+__device__ __forceinline__ void qk_64(const uint16_t* Ks, const bf16x8* qreg, int n, int k_swz,
+                                      f32x16* sacc)
+{
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const bf16x8 kr = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + n) * D +
+                                                               ((2 * kk) ^ k_swz) * 8);
+            sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr, qreg[kk], sacc[kb], 0, 0, 0);
+        }
+}
+
+template <int D>
+__global__ __launch_bounds__(128) void row_lse_kernel(MapArgs a, int nQB)
+{
+    constexpr int TILE = kBN * D;
+    constexpr int KSTEPS = D / 16;
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * TILE];
+    lds_u16* lds = (lds_u16*)smem;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int n = lane & 31, hh = lane >> 5;
+
+    const int bid = blockIdx.x;
+    const int qb = nQB - 1 - (bid % nQB);                    // long causal rows first
+    const int h = (bid / nQB) % a.H;
+    const int b = bid / (nQB * a.H);
+
+    const uint16_t* Qp = (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1];
+    const uint16_t* Kp = (const uint16_t*)a.K + (size_t)b * a.sk[0] + (size_t)h * a.sk[1];
+    const int sk_bytes = (int)a.sk[2] * 2;
+    const rsrc_t k_rsrc = make_rsrc(Kp, (unsigned)((a.Lk - 1) * sk_bytes + D * 2));
+
+    const int qrow = qb * 64 + wave * 32 + n;
+    const bool row_ok = qrow < a.Lq;
+    bf16x8 qreg[KSTEPS];
+    {
+        const uint16_t* qr = Qp + (size_t)(row_ok ? qrow : a.Lq - 1) * a.sq[2] + 8 * hh;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk)
+            qreg[kk] = *reinterpret_cast<const bf16x8*>(qr + 16 * kk);
+    }
+    const long long off = (long long)a.Lk - a.Lq;
+    const long long diag = (long long)qrow + off;            // last visible key if causal
+    int nkt = (a.Lk + 63) / 64;
+    if (a.causal) {
+        const long long block_diag = (long long)qb * 64 + 63 + off;
+        nkt = (int)min((long long)nkt, block_diag / 64 + 1);
+    }
+    const int k_swz = hh ^ swz_k<D>(n);
+    const float sc = a.scale * kLog2e;
+    float m = -INFINITY, lsum = 0.f;
+
+    issue_tile_loads<D, 2, false>(k_rsrc, lds, 0, sk_bytes, wave, lane);
+    for (int kt = 0; kt < nkt; ++kt) {
+        wait_vmem();                                         // tile kt has landed (also Q, first time)
+        __syncthreads();                                     // ... for everybody; tile kt-1 is consumed
+        if (kt + 1 < nkt)
+            issue_tile_loads<D, 2, false>(k_rsrc, lds + ((kt + 1) & 1) * TILE, (kt + 1) * 64,
+                                          sk_bytes, wave, lane);
+        f32x16 sacc[2];
+        qk_64<D>(smem + (kt & 1) * TILE, qreg, n, k_swz, sacc);
+
+        // keys of this tile that exist and that this query may see: a prefix of the tile
+        const long long k0 = (long long)kt * 64;
+        long long lim = (long long)a.Lk - k0;
+        if (a.causal) lim = min(lim, diag - k0 + 1);
+        const uint64_t word = lim >= 64 ? ~0ull : (lim <= 0 ? 0ull : (1ull << lim) - 1ull);
+        const uint64_t wsh = word >> (4 * hh);
+        const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int pos = 8 * (i / 4) + (i % 4);
+                const float sv = ((wbits[kb] >> pos) & 1u) ? sacc[kb][i] : -INFINITY;
+                sacc[kb][i] = sv;
+                tmax = fmaxf(tmax, sv);
+            }
+        {
+            const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+            tmax = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+        }
+        const float m_new = fmaxf(m, tmax);
+        const float msc = (m_new == -INFINITY) ? 0.f : m_new * sc;
+        const float alpha = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m * sc - msc);
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) psum += __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -msc));
+        lsum = lsum * alpha + psum;
+        m = m_new;
+    }
+    {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(lsum), __float_as_uint(lsum), false, false);
+        lsum = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    }
+    if (row_ok && hh == 0)
+        a.lse2[((size_t)b * a.H + h) * a.Lq + qrow] =
+            (m == -INFINITY) ? -INFINITY : fmaf(m, sc, __log2f(lsum));
+}
+
+template <int D>
+__global__ __launch_bounds__(128) void map_accumulate_kernel(MapArgs a, int nQB, int nKB)
+{
+    constexpr int TILE = kBN * D;
+    constexpr int KSTEPS = D / 16;
+    constexpr int OUT_LD = 68;                               // floats per staged output row (16-byte rows)
+    constexpr int OUT_ELEMS = 64 * OUT_LD * 2;               // in 2-byte units
+    constexpr int SMEM = 2 * TILE > OUT_ELEMS ? 2 * TILE : OUT_ELEMS;
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[SMEM];
+    lds_u16* lds = (lds_u16*)smem;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int n = lane & 31, hh = lane >> 5;
+
+    const int bid = blockIdx.x;
+    const int kt = bid % nKB;
+    const int qb = (bid / nKB) % nQB;
+    const int h = bid / (nKB * nQB);
+    const long long off = (long long)a.Lk - a.Lq;
+    if (a.causal && (long long)kt * 64 > (long long)qb * 64 + 63 + off) return;   // tile entirely hidden
+
+    const int qrow = qb * 64 + wave * 32 + n;
+    const int qload = qrow < a.Lq ? qrow : a.Lq - 1;
+    const int sk_bytes = (int)a.sk[2] * 2;
+    const unsigned k_bytes = (unsigned)((a.Lk - 1) * sk_bytes + D * 2);
+    const int k_swz = hh ^ swz_k<D>(n);
+    const float sc = a.scale * kLog2e;
+
+    auto q_row = [&](int b) {
+        return (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1] +
+               (size_t)qload * a.sq[2] + 8 * hh;
+    };
+    auto k_rsrc = [&](int b) {
+        return make_rsrc((const uint16_t*)a.K + (size_t)b * a.sk[0] + (size_t)h * a.sk[1], k_bytes);
+    };
+
+    f32x16 acc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
+
+    bf16x8 qcur[KSTEPS], qnext[KSTEPS];
+    float lcur, lnext = 0.f;
+    {
+        const uint16_t* qr = q_row(0);
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) qcur[kk] = *reinterpret_cast<const bf16x8*>(qr + 16 * kk);
+        lcur = a.lse2[(size_t)h * a.Lq + qload];
+        issue_tile_loads<D, 2, false>(k_rsrc(0), lds, kt * 64, sk_bytes, wave, lane);
+    }
+    for (int b = 0; b < a.B; ++b) {
+        wait_vmem();                                         // K tile, Q rows and lse of example b
+        __syncthreads();                                     // ... for everybody; the other stage is free
+        if (b + 1 < a.B) {                                   // example b + 1 travels under the arithmetic
+            const uint16_t* qr = q_row(b + 1);
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) qnext[kk] = *reinterpret_cast<const bf16x8*>(qr + 16 * kk);
+            lnext = a.lse2[((size_t)(b + 1) * a.H + h) * a.Lq + qload];
+            issue_tile_loads<D, 2, false>(k_rsrc(b + 1), lds + ((b + 1) & 1) * TILE, kt * 64,
+                                          sk_bytes, wave, lane);
+        }
+        f32x16 sacc[2];
+        qk_64<D>(smem + (b & 1) * TILE, qcur, n, k_swz, sacc);
+        // entries outside the map or hidden by causality are computed too (from zero keys or
+        // real ones) and dropped when the tile is written
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                acc[kb][i] += __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -lcur));
+        if (b + 1 < a.B) {
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS; ++kk) qcur[kk] = qnext[kk];
+            lcur = lnext;
+        }
+    }
+
+    // transpose through LDS: lanes hold columns of keys per query, memory wants rows of keys
+    __syncthreads();                                         // every wavefront is done with the K stages
+    float* outs = reinterpret_cast<float*>(smem);
+    {
+        const int row = wave * 32 + n;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float4 v = make_float4(acc[kb][4 * g], acc[kb][4 * g + 1], acc[kb][4 * g + 2],
+                                       acc[kb][4 * g + 3]);
+                *reinterpret_cast<float4*>(outs + row * OUT_LD + 32 * kb + 8 * g + 4 * hh) = v;
+            }
+    }
+    __syncthreads();
+    const bool vec_ok = (a.Lk & 3) == 0;                     // then every row of the map starts 16-byte aligned
+    const int c4 = (tid & 15) * 4;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+        const int r = pass * 8 + (tid >> 4);
+        const int q = qb * 64 + r;
+        if (q >= a.Lq) continue;
+        long long last = (long long)a.Lk - 1;                // last key of this row that is accumulated
+        if (a.causal) last = min(last, (long long)q + off);
+        const long long k = (long long)kt * 64 + c4;
+        if (k > last) continue;
+        const float4 v = *reinterpret_cast<const float4*>(outs + r * OUT_LD + c4);
+        float* dst = a.abar + ((size_t)h * a.Lq + q) * a.Lk + k;
+        if (vec_ok && k + 3 <= last) {
+            float4 o = *reinterpret_cast<float4*>(dst);
+            o.x = fmaf(a.weight, v.x, o.x);
+            o.y = fmaf(a.weight, v.y, o.y);
+            o.z = fmaf(a.weight, v.z, o.z);
+            o.w = fmaf(a.weight, v.w, o.w);
+            *reinterpret_cast<float4*>(dst) = o;
+        } else {
+            const float ve[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (k + e <= last) dst[e] = fmaf(a.weight, ve[e], dst[e]);
+        }
+    }
+}
+
+template <int D>
+hipError_t launch_d(const MapArgs& a, hipStream_t stream)
+{
+    const int nQB = (a.Lq + 63) / 64, nKB = (a.Lk + 63) / 64;
+    hipLaunchKernelGGL(row_lse_kernel<D>, dim3((unsigned)(a.B * a.H * nQB)), dim3(128), 0, stream, a, nQB);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(map_accumulate_kernel<D>, dim3((unsigned)(a.H * nQB * nKB)), dim3(128), 0,
+                       stream, a, nQB, nKB);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attention_maps(const MapArgs& a, hipStream_t stream)
+{
+    switch (a.D) {
+        case 32: return launch_d<32>(a, stream);
+        case 64: return launch_d<64>(a, stream);
+        case 128: return launch_d<128>(a, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace ap

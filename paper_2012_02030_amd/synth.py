@@ -157,6 +157,22 @@ def make_qkv(cfg: Config, which: str = "QKV", set_index: int = 0):
     return out
 
 
+def make_qk_positional(B: int, H: int, Lq: int, Lk: int, D: int, seed: int,
+                       strength: float = 1.0):
+    """Queries and keys whose attention concentrates next to the (bottom-right aligned) diagonal,
+    as the averaged self-attention patterns in the figure of Section 5.1 do: a sinusoidal
+    position code shared by Q and K (query i carries the code of position i + Lk - Lq, key j
+    that of position j, one random frequency set per head) plus standard-normal content.
+    float32 [B,H,Lq,D], [B,H,Lk,D]."""
+    rng = np.random.default_rng([SEED, 777, seed])
+    freq = np.exp(rng.uniform(np.log(1e-3), np.log(1.0), size=(H, D // 2)))
+    pos = np.arange(Lk, dtype=np.float64)[None, :, None] * freq[:, None, :]        # [H, Lk, D/2]
+    code = np.concatenate([np.sin(pos), np.cos(pos)], axis=-1) * strength            # [H, Lk, D]
+    Q = rng.standard_normal((B, H, Lq, D)) + code[None, :, Lk - Lq:, :]
+    K = rng.standard_normal((B, H, Lk, D)) + code[None]
+    return Q.astype(np.float32), K.astype(np.float32)
+
+
 def random_mask(H: int, Lq: int, Lk: int, density: float, seed: int) -> np.ndarray:
     """iid Bernoulli(density) keep-mask: the worst case for tile skipping (the paper's
     random-pruning control uses such patterns)."""

@@ -117,6 +117,55 @@ def test_schedule_arguments(L):
     assert _fwd(L, sched=C.pointer(good), dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
 
 
+def test_mask_construction_arguments(L):
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+    assert ap.ap_attention_maps_workspace_bytes(4, 16, 4096) == 4 * 16 * 4096 * 4
+    assert ap.ap_attention_maps_workspace_bytes(0, 16, 4096) == 0
+    ws = ap.ap_attention_maps_workspace_bytes(1, 2, 64)
+
+    def acc(**over):
+        a = dict(Q=fake, K=fake + 0x100000, dtype=ap.AP_BF16, B=1, H=2, Lq=64, Lk=64, D=64, sq=s, sk=s,
+                 causal=0, scale=0.0, weight=1.0, abar=fake, ws=fake, ws_bytes=ws)
+        a.update(over)
+        return L.ap_accumulate_attention_maps(a["Q"], a["K"], a["dtype"], a["B"], a["H"], a["Lq"],
+                                              a["Lk"], a["D"], a["sq"], a["sk"], a["causal"], a["scale"],
+                                              a["weight"], a["abar"], a["ws"], a["ws_bytes"], None)
+
+    assert acc(Q=None) == ap.AP_ERR_INVALID_ARG
+    assert acc(abar=None) == ap.AP_ERR_INVALID_ARG
+    assert acc(ws=None) == ap.AP_ERR_INVALID_ARG
+    assert acc(H=0) == ap.AP_ERR_INVALID_ARG
+    assert acc(dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    assert acc(D=48) == ap.AP_ERR_UNSUPPORTED
+    assert acc(causal=1, Lq=128, Lk=64) == ap.AP_ERR_INVALID_ARG
+    assert acc(abar=0x1004) == ap.AP_ERR_INVALID_ARG
+    assert acc(weight=float("inf")) == ap.AP_ERR_INVALID_ARG
+    assert acc(ws_bytes=ws - 1) == ap.AP_ERR_CAPACITY
+    bad = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 60)
+    assert acc(sk=bad) == ap.AP_ERR_INVALID_ARG
+
+    wp = ap.ap_prune_mask_workspace_bytes()
+    assert 4096 * 8 <= wp <= 4096 * 8 + 64
+
+    def prune(**over):
+        a = dict(abar=fake, H=2, Lq=64, Lk=64, causal=0, p=0.9, mask=fake, tau=fake, ws=fake, ws_bytes=wp)
+        a.update(over)
+        return L.ap_prune_mask(a["abar"], a["H"], a["Lq"], a["Lk"], a["causal"], a["p"], a["mask"],
+                               a["tau"], a["ws"], a["ws_bytes"], None)
+
+    assert prune(abar=None) == ap.AP_ERR_INVALID_ARG
+    assert prune(mask=None) == ap.AP_ERR_INVALID_ARG
+    assert prune(Lk=0) == ap.AP_ERR_INVALID_ARG
+    assert prune(p=-0.1) == ap.AP_ERR_INVALID_ARG
+    assert prune(p=1.5) == ap.AP_ERR_INVALID_ARG
+    assert prune(p=float("nan")) == ap.AP_ERR_INVALID_ARG
+    assert prune(causal=1, Lq=128, Lk=64) == ap.AP_ERR_INVALID_ARG
+    assert prune(abar=0x1004) == ap.AP_ERR_INVALID_ARG
+    assert prune(mask=0x1002) == ap.AP_ERR_INVALID_ARG
+    assert prune(ws_bytes=wp - 1) == ap.AP_ERR_CAPACITY
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ap, "_lib", None)
     monkeypatch.setattr(ap, "LIB_PATH", "/nonexistent/libap_mi355x.so")
