@@ -39,6 +39,8 @@ def parse():
     p.add_argument("--no-sched", action="store_true", help="walk the layout itself instead of the visit schedule")
     p.add_argument("--only", action="store_true", help="skip the per-config table and the CPU baseline")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    p.add_argument("--no-mask-construction", action="store_true",
+                   help="skip the timing of the mask-construction kernels (Eq. (1), Eq. (2))")
     p.add_argument("--copy-calibration", action="store_true",
                    help="also launch one plain 256 MiB device copy (reference point for HBM byte counters)")
     return p.parse_args()
@@ -228,6 +230,70 @@ def main():
         keep_for_parity = (sets[0], outs, lses, layout, sched)
         return res, keep_for_parity
 
+    def run_mask_construction(cfg, steps):
+        """Eq. (1) accumulation of one batch into the mean map and Eq. (2) threshold + mask, at
+        cfg's shape, on position-coded synthetic Q and K; then the layout of the resulting mask."""
+        if cfg.dtype != "bf16":
+            return None
+        qn, kn = synth.make_qk_positional(cfg.B, cfg.H, cfg.Lq, cfg.Lk, cfg.D, seed=cfg.index)
+        q = torch.from_numpy(qn).to(torch.bfloat16).to(dev)
+        k = torch.from_numpy(kn).to(torch.bfloat16).to(dev)
+        del qn, kn
+        abar = torch.zeros((cfg.H, cfg.Lq, cfg.Lk), dtype=torch.float32, device=dev)
+        p = 1.0 - cfg.keep
+
+        def timed(fn, n):
+            fn()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            torch.cuda.synchronize()
+            evs[0].record()
+            for i in range(n):
+                fn()
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            return float(np.mean([evs[i].elapsed_time(evs[i + 1]) for i in range(n)]))
+
+        acc_ms = timed(lambda: ap.ap_accumulate_attention_maps(q, k, abar=abar, causal=cfg.causal,
+                                                               weight=1.0 / cfg.B), steps)
+        abar.zero_()
+        ap.ap_accumulate_attention_maps(q, k, abar=abar, causal=cfg.causal, weight=1.0 / cfg.B)
+        keep = {}
+
+        def prune():
+            keep["mask"], keep["tau"] = ap.ap_prune_mask(abar, p, causal=cfg.causal)
+
+        prune_ms = timed(prune, steps)
+        lay_ms = timed(lambda: ap.ap_build_layout(keep["mask"], args.block_m, 64), steps)
+        if cfg.causal:
+            vis = cfg.H * sum(min(cfg.Lk, i + 1 + cfg.Lk - cfg.Lq) for i in range(cfg.Lq))
+        else:
+            vis = cfg.H * cfg.Lq * cfg.Lk
+        total = cfg.H * cfg.Lq * cfg.Lk
+        # map read + written once, Q and K read once, row log-sum-exp written and read once
+        acc_bytes = 8 * vis + 2 * cfg.B * cfg.H * cfg.D * (cfg.Lq + cfg.Lk) + 8 * cfg.B * cfg.H * cfg.Lq
+        acc_flop = 2 * 2.0 * cfg.D * vis * cfg.B                          # scores are formed twice
+        # selection reads every participating entry at least once, the compare once more; 1 mask byte each
+        prune_bytes = 8 * vis + total
+        kept = int(keep["mask"].sum().item())
+        return {
+            "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D, "causal": cfg.causal},
+            "prune_fraction": p,
+            "accumulate_ms": acc_ms,
+            "accumulate_alg_bytes": acc_bytes,
+            "accumulate_gbs": acc_bytes / (acc_ms * 1e-3) / 1e9,
+            "accumulate_hbm_frac": acc_bytes / (acc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "accumulate_tflops": acc_flop / (acc_ms * 1e-3) / 1e12,
+            "prune_mask_ms": prune_ms,
+            "prune_mask_alg_bytes": prune_bytes,
+            "prune_mask_gbs": prune_bytes / (prune_ms * 1e-3) / 1e9,
+            "prune_mask_hbm_frac": prune_bytes / (prune_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "layout_ms": lay_ms,
+            "tau": float(keep["tau"].item()),
+            "kept_entries": kept,
+            "kept_fraction_of_visible": kept / float(vis),
+            "tiles_stored": int(ap.ap_build_layout(keep["mask"], args.block_m, 64).nnz.item()),
+        }
+
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
@@ -285,6 +351,12 @@ def main():
             torch.cuda.empty_cache()
             per_config[name] = res
 
+    mask_construction = None
+    if not args.only and not args.no_mask_construction:
+        log("timing mask construction at the", head.name, "shape ...")
+        mask_construction = run_mask_construction(head, 10)
+        torch.cuda.empty_cache()
+
     out = {
         "metric": "kept-entry TFLOP/s of masked attention fwd (ms/call and speedup vs dense-mask run alongside)",
         "value": head_res["kept_tflops"],
@@ -316,6 +388,7 @@ def main():
                                "unit": "TFLOP/s", "frac": head_res["dense_mfma_frac"]},
         "cpu_baseline": cpu,
         "parity": parity,
+        "mask_construction": mask_construction,
         "per_config": per_config,
     }
     print(json.dumps(out), flush=True)

@@ -3,13 +3,13 @@
 // The attention matrix of one example, A_b = softmax(Q_b K_b^T / sqrt(d_k)), is never stored:
 // it would be B*H*Lq*Lk probabilities.  Two kernels instead:
 //
-//   row_lse_kernel         one workgroup per (example, head, 64 queries): walks all key tiles,
+//   row_lse_kernel         one workgroup per (example, head, 128 queries): walks all key tiles,
 //                          S^T = K Q^T on the matrix cores, keeps the online row maximum and row
 //                          sum, and writes the row's log-sum-exp (base 2) to the workspace.
-//   map_accumulate_kernel  one workgroup per (head, 64 queries, 64 keys): loops over the examples,
-//                          recomputes the 64x64 scores, P = exp2(s - lse), and sums P in
-//                          registers; the running map in memory is read and written once per
-//                          call, whatever the batch size.
+//   map_accumulate_kernel  one workgroup per (head, 128 queries, 128 keys): loops over the
+//                          examples, recomputes the scores tile by tile, P = exp2(s - lse), and
+//                          sums P in registers; the running map in memory is read and written
+//                          once per call, whatever the batch size.
 //
 // Both use the score layout of the attention kernel: a wavefront owns 32 queries, lane l holds
 // query l % 32 and, of each 32-key block, the keys 8*(i/4) + 4*(l/32) + i%4 (i = 0..15).
@@ -31,23 +31,59 @@ template <int D>
 __device__ __forceinline__ void qk_64(const uint16_t* Ks, const bf16x8* qreg, int n, int k_swz,
                                       f32x16* sacc)
 {
+    constexpr int KSTEPS = D / 16;
+    constexpr int AHEAD = KSTEPS < 3 ? KSTEPS : 3;           // key operands requested this many steps early
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+    bf16x8 kreg[KSTEPS][2];
+    auto read_step = [&](int kk) {
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk)
+        for (int kb = 0; kb < 2; ++kb)
+            kreg[kk][kb] = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + n) * D + ((2 * kk) ^ k_swz) * 8);
+    };
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            const bf16x8 kr = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + n) * D +
-                                                               ((2 * kk) ^ k_swz) * 8);
-            sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr, qreg[kk], sacc[kb], 0, 0, 0);
-        }
+    for (int kk = 0; kk < AHEAD; ++kk) read_step(kk);
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        if (kk + AHEAD < KSTEPS) read_step(kk + AHEAD);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+            sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk][kb], qreg[kk], sacc[kb], 0, 0, 0);
+    }
+    // pin that order, so that LDS latency is paid once per tile and not once per step
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * AHEAD, 0);
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        if (kk + AHEAD < KSTEPS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    }
 }
 
-template <int D>
-__global__ __launch_bounds__(128) void row_lse_kernel(MapArgs a, int nQB)
+// Makes the compiler place its own wait for these loaded registers here (right after a
+// wait_vmem(), where it costs nothing) instead of in front of their first real use, where it
+// would also wait for the tile loads issued in between.
+template <int N>
+__device__ __forceinline__ void settle(bf16x8* q)
 {
+#pragma unroll
+    for (int kk = 0; kk < N; ++kk) asm volatile("" : "+v"(q[kk]));
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  This bijection gives
+// every XCD one contiguous range of the linear workgroup index, so that the workgroups that
+// share the K and Q rows of a head (and example) also share an L2.
+__device__ __forceinline__ int xcd_contiguous(int bid, int grid)
+{
+    const int x = bid & 7, q = grid >> 3, r = grid & 7;
+    return x * q + min(x, r) + (bid >> 3);
+}
+
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void row_lse_kernel(MapArgs a, int nQB)
+{
+    constexpr int BM = 32 * NW;
     constexpr int TILE = kBN * D;
     constexpr int KSTEPS = D / 16;
     __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * TILE];
@@ -58,7 +94,7 @@ __global__ __launch_bounds__(128) void row_lse_kernel(MapArgs a, int nQB)
     const int lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
 
-    const int bid = blockIdx.x;
+    const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
     const int qb = nQB - 1 - (bid % nQB);                    // long causal rows first
     const int h = (bid / nQB) % a.H;
     const int b = bid / (nQB * a.H);
@@ -68,7 +104,7 @@ __global__ __launch_bounds__(128) void row_lse_kernel(MapArgs a, int nQB)
     const int sk_bytes = (int)a.sk[2] * 2;
     const rsrc_t k_rsrc = make_rsrc(Kp, (unsigned)((a.Lk - 1) * sk_bytes + D * 2));
 
-    const int qrow = qb * 64 + wave * 32 + n;
+    const int qrow = qb * BM + wave * 32 + n;
     const bool row_ok = qrow < a.Lq;
     bf16x8 qreg[KSTEPS];
     {
@@ -81,20 +117,22 @@ __global__ __launch_bounds__(128) void row_lse_kernel(MapArgs a, int nQB)
     const long long diag = (long long)qrow + off;            // last visible key if causal
     int nkt = (a.Lk + 63) / 64;
     if (a.causal) {
-        const long long block_diag = (long long)qb * 64 + 63 + off;
+        const long long block_diag = (long long)qb * BM + (BM - 1) + off;
         nkt = (int)min((long long)nkt, block_diag / 64 + 1);
     }
     const int k_swz = hh ^ swz_k<D>(n);
     const float sc = a.scale * kLog2e;
     float m = -INFINITY, lsum = 0.f;
 
-    issue_tile_loads<D, 2, false>(k_rsrc, lds, 0, sk_bytes, wave, lane);
+    wait_vmem();
+    settle<KSTEPS>(qreg);
+    issue_tile_loads<D, NW, false>(k_rsrc, lds, 0, sk_bytes, wave, lane);
     for (int kt = 0; kt < nkt; ++kt) {
-        wait_vmem();                                         // tile kt has landed (also Q, first time)
+        wait_vmem();                                         // tile kt has landed
         __syncthreads();                                     // ... for everybody; tile kt-1 is consumed
         if (kt + 1 < nkt)
-            issue_tile_loads<D, 2, false>(k_rsrc, lds + ((kt + 1) & 1) * TILE, (kt + 1) * 64,
-                                          sk_bytes, wave, lane);
+            issue_tile_loads<D, NW, false>(k_rsrc, lds + ((kt + 1) & 1) * TILE, (kt + 1) * 64,
+                                           sk_bytes, wave, lane);
         f32x16 sacc[2];
         qk_64<D>(smem + (kt & 1) * TILE, qreg, n, k_swz, sacc);
 
@@ -102,19 +140,26 @@ __global__ __launch_bounds__(128) void row_lse_kernel(MapArgs a, int nQB)
         const long long k0 = (long long)kt * 64;
         long long lim = (long long)a.Lk - k0;
         if (a.causal) lim = min(lim, diag - k0 + 1);
-        const uint64_t word = lim >= 64 ? ~0ull : (lim <= 0 ? 0ull : (1ull << lim) - 1ull);
-        const uint64_t wsh = word >> (4 * hh);
-        const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
         float tmax = -INFINITY;
+        if (__ballot(lim < 64) == 0) {                       // whole tile visible to the whole wavefront
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int pos = 8 * (i / 4) + (i % 4);
-                const float sv = ((wbits[kb] >> pos) & 1u) ? sacc[kb][i] : -INFINITY;
-                sacc[kb][i] = sv;
-                tmax = fmaxf(tmax, sv);
-            }
+                for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sacc[kb][i]);
+        } else {
+            const uint64_t word = lim >= 64 ? ~0ull : (lim <= 0 ? 0ull : (1ull << lim) - 1ull);
+            const uint64_t wsh = word >> (4 * hh);
+            const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int pos = 8 * (i / 4) + (i % 4);
+                    const float sv = ((wbits[kb] >> pos) & 1u) ? sacc[kb][i] : -INFINITY;
+                    sacc[kb][i] = sv;
+                    tmax = fmaxf(tmax, sv);
+                }
+        }
         {
             const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
             tmax = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
@@ -139,13 +184,17 @@ __global__ __launch_bounds__(128) void row_lse_kernel(MapArgs a, int nQB)
             (m == -INFINITY) ? -INFINITY : fmaf(m, sc, __log2f(lsum));
 }
 
-template <int D>
-__global__ __launch_bounds__(128) void map_accumulate_kernel(MapArgs a, int nQB, int nKB)
+// One workgroup: 32*NW queries x KT*64 keys of one head.  The Q rows of an example are loaded
+// once for all KT key tiles, every K tile serves all NW wavefronts, and the KT partial maps stay
+// in registers over the examples.
+template <int D, int NW, int KT>
+__global__ __launch_bounds__(64 * NW) void map_accumulate_kernel(MapArgs a, int nQB, int nKG)
 {
+    constexpr int BM = 32 * NW;
     constexpr int TILE = kBN * D;
     constexpr int KSTEPS = D / 16;
     constexpr int OUT_LD = 68;                               // floats per staged output row (16-byte rows)
-    constexpr int OUT_ELEMS = 64 * OUT_LD * 2;               // in 2-byte units
+    constexpr int OUT_ELEMS = BM * OUT_LD * 2;               // in 2-byte units
     constexpr int SMEM = 2 * TILE > OUT_ELEMS ? 2 * TILE : OUT_ELEMS;
     __shared__ __attribute__((aligned(1024))) uint16_t smem[SMEM];
     lds_u16* lds = (lds_u16*)smem;
@@ -155,14 +204,20 @@ __global__ __launch_bounds__(128) void map_accumulate_kernel(MapArgs a, int nQB,
     const int lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
 
-    const int bid = blockIdx.x;
-    const int kt = bid % nKB;
-    const int qb = (bid / nKB) % nQB;
-    const int h = bid / (nKB * nQB);
+    const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int kg = bid % nKG;
+    const int qb = (bid / nKG) % nQB;
+    const int h = bid / (nKG * nQB);
     const long long off = (long long)a.Lk - a.Lq;
-    if (a.causal && (long long)kt * 64 > (long long)qb * 64 + 63 + off) return;   // tile entirely hidden
+    const int key0 = kg * (KT * 64);                         // first key of this workgroup
+    int n_sub = min(KT, (a.Lk - key0 + 63) / 64);            // key tiles that exist ...
+    if (a.causal) {                                          // ... and that some query of the block sees
+        const long long block_diag = (long long)qb * BM + (BM - 1) + off;
+        if (block_diag < key0) return;
+        n_sub = (int)min((long long)n_sub, (block_diag - key0) / 64 + 1);
+    }
 
-    const int qrow = qb * 64 + wave * 32 + n;
+    const int qrow = qb * BM + wave * 32 + n;
     const int qload = qrow < a.Lq ? qrow : a.Lq - 1;
     const int sk_bytes = (int)a.sk[2] * 2;
     const unsigned k_bytes = (unsigned)((a.Lk - 1) * sk_bytes + D * 2);
@@ -173,92 +228,128 @@ __global__ __launch_bounds__(128) void map_accumulate_kernel(MapArgs a, int nQB,
         return (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1] +
                (size_t)qload * a.sq[2] + 8 * hh;
     };
-    auto k_rsrc = [&](int b) {
-        return make_rsrc((const uint16_t*)a.K + (size_t)b * a.sk[0] + (size_t)h * a.sk[1], k_bytes);
+    auto issue_k = [&](int b, int sub, int stage) {
+        const rsrc_t rs = make_rsrc((const uint16_t*)a.K + (size_t)b * a.sk[0] + (size_t)h * a.sk[1], k_bytes);
+        issue_tile_loads<D, NW, false>(rs, lds + stage * TILE, key0 + sub * 64, sk_bytes, wave, lane);
     };
 
-    f32x16 acc[2];
+    f32x16 acc[KT][2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int sub = 0; sub < KT; ++sub)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[kb][i] = 0.f;
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[sub][kb][i] = 0.f;
 
-    bf16x8 qcur[KSTEPS], qnext[KSTEPS];
+    bf16x8 qcur[KSTEPS];
     float lcur, lnext = 0.f;
     {
         const uint16_t* qr = q_row(0);
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) qcur[kk] = *reinterpret_cast<const bf16x8*>(qr + 16 * kk);
         lcur = a.lse2[(size_t)h * a.Lq + qload];
-        issue_tile_loads<D, 2, false>(k_rsrc(0), lds, kt * 64, sk_bytes, wave, lane);
+        issue_k(0, 0, 0);
     }
+    int stage = 0;
     for (int b = 0; b < a.B; ++b) {
-        wait_vmem();                                         // K tile, Q rows and lse of example b
-        __syncthreads();                                     // ... for everybody; the other stage is free
-        if (b + 1 < a.B) {                                   // example b + 1 travels under the arithmetic
-            const uint16_t* qr = q_row(b + 1);
 #pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) qnext[kk] = *reinterpret_cast<const bf16x8*>(qr + 16 * kk);
-            lnext = a.lse2[((size_t)(b + 1) * a.H + h) * a.Lq + qload];
-            issue_tile_loads<D, 2, false>(k_rsrc(b + 1), lds + ((b + 1) & 1) * TILE, kt * 64,
-                                          sk_bytes, wave, lane);
-        }
-        f32x16 sacc[2];
-        qk_64<D>(smem + (b & 1) * TILE, qcur, n, k_swz, sacc);
-        // entries outside the map or hidden by causality are computed too (from zero keys or
-        // real ones) and dropped when the tile is written
+        for (int sub = 0; sub < KT; ++sub) {
+            if (sub >= n_sub) continue;                      // uniform over the workgroup
+            wait_vmem();                                     // this K tile (and new Q rows) have landed
+            settle<KSTEPS>(qcur);
+            asm volatile("" : "+v"(lnext), "+v"(lcur));
+            if (sub == 0 && b > 0) lcur = lnext;
+            __syncthreads();                                 // ... for everybody; the other stage is free
+            const bool last = sub + 1 == n_sub;
+            if (!last) issue_k(b, sub + 1, stage ^ 1);       // the next tile travels under the arithmetic
+            else if (b + 1 < a.B) issue_k(b + 1, 0, stage ^ 1);
+            f32x16 sacc[2];
+            qk_64<D>(smem + stage * TILE, qcur, n, k_swz, sacc);
+            if (last && b + 1 < a.B) {                       // Q rows and lse of the next example
+                const uint16_t* qr = q_row(b + 1);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+                for (int kk = 0; kk < KSTEPS; ++kk) qcur[kk] = *reinterpret_cast<const bf16x8*>(qr + 16 * kk);
+                lnext = a.lse2[((size_t)(b + 1) * a.H + h) * a.Lq + qload];
+            }
+            // entries outside the map or hidden by causality are computed too (from zero keys or
+            // real ones) and dropped when the tile is written
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-                acc[kb][i] += __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -lcur));
-        if (b + 1 < a.B) {
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int kk = 0; kk < KSTEPS; ++kk) qcur[kk] = qnext[kk];
-            lcur = lnext;
+                for (int i = 0; i < 16; ++i)
+                    acc[sub][kb][i] += __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -lcur));
+            stage ^= 1;
         }
     }
 
     // transpose through LDS: lanes hold columns of keys per query, memory wants rows of keys
-    __syncthreads();                                         // every wavefront is done with the K stages
     float* outs = reinterpret_cast<float*>(smem);
-    {
-        const int row = wave * 32 + n;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float4 v = make_float4(acc[kb][4 * g], acc[kb][4 * g + 1], acc[kb][4 * g + 2],
-                                       acc[kb][4 * g + 3]);
-                *reinterpret_cast<float4*>(outs + row * OUT_LD + 32 * kb + 8 * g + 4 * hh) = v;
-            }
-    }
-    __syncthreads();
     const bool vec_ok = (a.Lk & 3) == 0;                     // then every row of the map starts 16-byte aligned
     const int c4 = (tid & 15) * 4;
 #pragma unroll
-    for (int pass = 0; pass < 8; ++pass) {
-        const int r = pass * 8 + (tid >> 4);
-        const int q = qb * 64 + r;
-        if (q >= a.Lq) continue;
-        long long last = (long long)a.Lk - 1;                // last key of this row that is accumulated
-        if (a.causal) last = min(last, (long long)q + off);
-        const long long k = (long long)kt * 64 + c4;
-        if (k > last) continue;
-        const float4 v = *reinterpret_cast<const float4*>(outs + r * OUT_LD + c4);
-        float* dst = a.abar + ((size_t)h * a.Lq + q) * a.Lk + k;
-        if (vec_ok && k + 3 <= last) {
-            float4 o = *reinterpret_cast<float4*>(dst);
-            o.x = fmaf(a.weight, v.x, o.x);
-            o.y = fmaf(a.weight, v.y, o.y);
-            o.z = fmaf(a.weight, v.z, o.z);
-            o.w = fmaf(a.weight, v.w, o.w);
-            *reinterpret_cast<float4*>(dst) = o;
-        } else {
-            const float ve[4] = {v.x, v.y, v.z, v.w};
+    for (int sub = 0; sub < KT; ++sub) {
+        if (sub >= n_sub) continue;
+        __syncthreads();                                     // K stages / previous staged tile are consumed
+        {
+            const int row = wave * 32 + n;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (k + e <= last) dst[e] = fmaf(a.weight, ve[e], dst[e]);
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    float4 v = make_float4(acc[sub][kb][4 * g], acc[sub][kb][4 * g + 1],
+                                           acc[sub][kb][4 * g + 2], acc[sub][kb][4 * g + 3]);
+                    *reinterpret_cast<float4*>(outs + row * OUT_LD + 32 * kb + 8 * g + 4 * hh) = v;
+                }
+        }
+        __syncthreads();
+        // a tile that lies inside the map and below the causal limit for all its rows takes the
+        // branch-free path: all 8 loads of a thread are in flight before the first is used
+        const long long k_first = (long long)key0 + sub * 64;
+        bool interior = vec_ok && qb * BM + BM <= a.Lq && k_first + 63 <= (long long)a.Lk - 1;
+        if (a.causal) interior = interior && k_first + 63 <= (long long)qb * BM + off;
+        if (interior) {
+            float* base = a.abar + ((size_t)h * a.Lq + (size_t)qb * BM + (tid >> 4)) * a.Lk + k_first + c4;
+            float4 o[8];
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass)
+                o[pass] = *reinterpret_cast<const float4*>(base + (size_t)pass * (4 * NW) * a.Lk);
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass) {
+                const float4 v = *reinterpret_cast<const float4*>(outs + (pass * (4 * NW) + (tid >> 4)) * OUT_LD + c4);
+                o[pass].x = fmaf(a.weight, v.x, o[pass].x);
+                o[pass].y = fmaf(a.weight, v.y, o[pass].y);
+                o[pass].z = fmaf(a.weight, v.z, o[pass].z);
+                o[pass].w = fmaf(a.weight, v.w, o[pass].w);
+            }
+#pragma unroll
+            for (int pass = 0; pass < 8; ++pass)
+                *reinterpret_cast<float4*>(base + (size_t)pass * (4 * NW) * a.Lk) = o[pass];
+            continue;
+        }
+#pragma unroll
+        for (int pass = 0; pass < 8; ++pass) {
+            const int r = pass * (4 * NW) + (tid >> 4);
+            const int q = qb * BM + r;
+            if (q >= a.Lq) continue;
+            long long last_key = (long long)a.Lk - 1;        // last key of this row that is accumulated
+            if (a.causal) last_key = min(last_key, (long long)q + off);
+            const long long k = k_first + c4;
+            if (k > last_key) continue;
+            const float4 v = *reinterpret_cast<const float4*>(outs + r * OUT_LD + c4);
+            float* dst = a.abar + ((size_t)h * a.Lq + q) * a.Lk + k;
+            if (vec_ok && k + 3 <= last_key) {
+                float4 o = *reinterpret_cast<float4*>(dst);
+                o.x = fmaf(a.weight, v.x, o.x);
+                o.y = fmaf(a.weight, v.y, o.y);
+                o.z = fmaf(a.weight, v.z, o.z);
+                o.w = fmaf(a.weight, v.w, o.w);
+                *reinterpret_cast<float4*>(dst) = o;
+            } else {
+                const float ve[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (k + e <= last_key) dst[e] = fmaf(a.weight, ve[e], dst[e]);
+            }
         }
     }
 }
@@ -266,12 +357,14 @@ __global__ __launch_bounds__(128) void map_accumulate_kernel(MapArgs a, int nQB,
 template <int D>
 hipError_t launch_d(const MapArgs& a, hipStream_t stream)
 {
-    const int nQB = (a.Lq + 63) / 64, nKB = (a.Lk + 63) / 64;
-    hipLaunchKernelGGL(row_lse_kernel<D>, dim3((unsigned)(a.B * a.H * nQB)), dim3(128), 0, stream, a, nQB);
+    constexpr int NW = 4, KT = 2;
+    const int nQB = (a.Lq + 32 * NW - 1) / (32 * NW), nKG = (a.Lk + 64 * KT - 1) / (64 * KT);
+    hipLaunchKernelGGL((row_lse_kernel<D, NW>), dim3((unsigned)(a.B * a.H * nQB)), dim3(64 * NW), 0,
+                       stream, a, nQB);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(map_accumulate_kernel<D>, dim3((unsigned)(a.H * nQB * nKB)), dim3(128), 0,
-                       stream, a, nQB, nKB);
+    hipLaunchKernelGGL((map_accumulate_kernel<D, NW, KT>), dim3((unsigned)(a.H * nQB * nKG)),
+                       dim3(64 * NW), 0, stream, a, nQB, nKG);
     return hipGetLastError();
 }
 
