@@ -225,7 +225,7 @@ ap_status ap_prune_mask(const float* abar, int H, int Lq, int Lk, int causal, do
     const double want = floor(prune_fraction * (double)N);
     const bool none = want >= (double)N;
     const unsigned long long rank = none ? 0ull : (unsigned long long)want;
-    return ap::launch_prune_mask(abar, H, Lq, Lk, causal ? 1 : 0, rank, none, mask, tau_out, workspace,
+    return ap::launch_prune_mask(abar, H, Lq, Lk, causal ? 1 : 0, rank, N, none, mask, tau_out, workspace,
                                  (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 

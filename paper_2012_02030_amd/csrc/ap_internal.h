@@ -66,9 +66,9 @@ hipError_t launch_attention_maps(const MapArgs& a, hipStream_t stream);
 
 // ---- mask construction: percentile threshold and mask (ap_threshold.hip)
 size_t prune_mask_workspace_bytes();
-// rank: 0-based position of tau among the participating entries; none: prune everything
+// rank: 0-based position of tau among the n participating entries; none: prune everything
 hipError_t launch_prune_mask(const float* abar, int H, int Lq, int Lk, int causal,
-                             unsigned long long rank, bool none, uint8_t* mask, float* tau_out,
-                             void* workspace, hipStream_t stream);
+                             unsigned long long rank, unsigned long long n, bool none, uint8_t* mask,
+                             float* tau_out, void* workspace, hipStream_t stream);
 
 }  // namespace ap

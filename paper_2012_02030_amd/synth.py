@@ -173,6 +173,21 @@ def make_qk_positional(B: int, H: int, Lq: int, Lk: int, D: int, seed: int,
     return Q.astype(np.float32), K.astype(np.float32)
 
 
+def make_mean_map(H: int, Lq: int, Lk: int, seed: int) -> np.ndarray:
+    """float32 [H,Lq,Lk] stand-in for a layer's mean attention maps: a per-head band that decays
+    away from the (bottom-right aligned) diagonal plus a small floor, times uniform noise.
+    Rows are not normalised; only the order of the values matters to the threshold."""
+    out = np.empty((H, Lq, Lk), dtype=np.float32)
+    d = np.abs(np.arange(Lq, dtype=np.float32)[:, None] + np.float32(Lk - Lq)
+               - np.arange(Lk, dtype=np.float32)[None, :])
+    for h in range(H):
+        rng = np.random.default_rng([SEED, 555, seed, h])
+        width = np.float32(4.0 * (1 + h % 5))
+        noise = rng.random((Lq, Lk), dtype=np.float32) + np.float32(0.05)
+        out[h] = (np.exp(-d / width) + np.float32(1e-3)) * noise
+    return out
+
+
 def random_mask(H: int, Lq: int, Lk: int, density: float, seed: int) -> np.ndarray:
     """iid Bernoulli(density) keep-mask: the worst case for tile skipping (the paper's
     random-pruning control uses such patterns)."""

@@ -146,7 +146,7 @@ def test_mask_construction_arguments(L):
     assert acc(sk=bad) == ap.AP_ERR_INVALID_ARG
 
     wp = ap.ap_prune_mask_workspace_bytes()
-    assert 4096 * 8 <= wp <= 4096 * 8 + 64
+    assert wp == 64 + 32768 * 8 + (1 << 20) * (4 + 8)      # state, histogram, candidate keys and indices
 
     def prune(**over):
         a = dict(abar=fake, H=2, Lq=64, Lk=64, causal=0, p=0.9, mask=fake, tau=fake, ws=fake, ws_bytes=wp)

@@ -139,6 +139,21 @@ def test_prune_mask_values_that_differ_in_the_last_bits():
         check_prune(a, p, False)
 
 
+@pytest.mark.parametrize("spread", [3000, 3, 1])
+def test_prune_mask_more_ties_than_the_candidate_buffer_holds(spread):
+    """Over two million entries inside one 1 %-wide value interval: the selection has to fix
+    more digits with further sweeps (spread 3000), down to the last bit (spread 3), or finds
+    every entry equal (spread 1)."""
+    rng = np.random.default_rng(43)
+    shape = (2, 1024, 1024)
+    steps = rng.integers(0, spread, size=shape).astype(np.uint32)
+    a = (np.float32(0.5).view(np.uint32) + steps).view(np.float32).reshape(shape)
+    a[0, :7, :5] = 0.0                                                    # a few entries elsewhere
+    a[1, 5, 100:140] = 0.75
+    for p, causal in ((0.5, False), (0.9, True), (0.0, False)):
+        check_prune(a, p, causal)
+
+
 def test_mask_feeds_layout_and_attention_end_to_end():
     """Q, K -> mean map -> mask -> layout on the GPU; entries whose oracle mean is not within
     the map tolerance of the oracle's threshold must agree with the oracle's mask."""
@@ -159,3 +174,29 @@ def test_mask_feeds_layout_and_attention_end_to_end():
     assert abs(int(got.sum()) - (n - int(np.floor(p * n)))) <= 4            # exact up to ties at tau
     from gpu_util import assert_layout_equal
     assert_layout_equal(lay, got)
+
+
+# --- the benchmark's shape and launch configuration ---------------------------------------------------
+
+def test_full_size_mean_map_rows_sampled_against_oracle():
+    """C5's shape (B4 H16 L4096 D128 causal): rows sum to 1, hidden entries stay untouched, and
+    windows of rows of three heads match the oracle element by element."""
+    cfg = synth.CONFIGS["C5"]
+    Q, K = synth.make_qk_positional(cfg.B, cfg.H, cfg.Lq, cfg.Lk, cfg.D, seed=cfg.index)
+    abar, rq, rk = run_maps(Q, K, True)
+    rs = abar.sum(-1)
+    assert float((rs - 1.0).abs().max()) <= MAP_TOL
+    assert float(abar.min()) >= 0.0
+    upper = torch.triu(torch.ones(cfg.Lq, cfg.Lk, dtype=torch.bool, device="cuda"), diagonal=1)
+    assert float(abar[:, upper].abs().max()) == 0.0                       # never written
+    for h, r0, r1 in ((0, 0, 8), (7, 2040, 2056), (15, 4088, 4096), (3, 1000, 1003)):
+        ref = oracle.attention_maps(rq[:, h:h + 1, r0:r1], rk[:, h:h + 1, :r1], causal=True).mean(0)[0]
+        got = abar[h, r0:r1, :r1].double().cpu().numpy()
+        assert np.abs(got - ref).max() <= MAP_TOL
+
+
+def test_full_size_threshold_and_mask_bit_exact():
+    """H16 x 4096 x 4096 causal map (the benchmark's shape), prune 90 %: tau and every mask byte
+    equal the oracle's on the same float32 input."""
+    a = synth.make_mean_map(16, 4096, 4096, seed=5)
+    check_prune(a, 0.9, True)
