@@ -39,6 +39,8 @@ def parse():
     p.add_argument("--no-sched", action="store_true", help="walk the layout itself instead of the visit schedule")
     p.add_argument("--only", action="store_true", help="skip the per-config table and the CPU baseline")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    p.add_argument("--only-mask-construction", action="store_true",
+                   help="time only the mask-construction kernels at the workload's shape and print their figures")
     p.add_argument("--no-mask-construction", action="store_true",
                    help="skip the timing of the mask-construction kernels (Eq. (1), Eq. (2))")
     p.add_argument("--copy-calibration", action="store_true",
@@ -303,6 +305,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.only_mask_construction:
+        print(json.dumps({"mask_construction": run_mask_construction(synth.CONFIGS[args.workload], args.steps)}),
+              flush=True)
+        return
 
     # ---------------------------------------------------------------- headline workload
     head = synth.CONFIGS[args.workload]
