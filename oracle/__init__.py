@@ -14,6 +14,9 @@ build_layout       block-sparse layout (block rows, block columns, per-block ele
 macs_fraction      Appendix A's multiply-accumulate count, the model behind Eq. (3)
 kept_entry_flops   4*D flops per kept (query, key) connection: both N^2-sized products
 
+The backward pass (gradients of the masked-attention equation) is in ``backward.py`` (numpy):
+masked_attention_backward.
+
 Mask construction (Section 3.2, Eq. (1) and Eq. (2)) is in ``mask_construction.py`` (numpy):
 attention_maps, mean_attention_map, percentile_threshold, prune_mask.
 """
@@ -25,6 +28,7 @@ import subprocess
 
 import numpy as np
 
+from .backward import masked_attention_backward  # noqa: F401
 from .mask_construction import (attention_maps, mean_attention_map,  # noqa: F401
                                 percentile_threshold, prune_mask)
 
