@@ -173,6 +173,58 @@ ap_status ap_sparse_attn_fwd(const void *Q, const void *K, const void *V, void *
                              void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Backward pass of masked attention (Section 3.2, algorithm step 4: the pruned model F' is
+ * trained, which needs the gradients of the masked-attention equation).
+ *
+ * With P_ij = exp(s_ij - lse_i) on kept, visible entries and 0 elsewhere (s and lse as in
+ * ap_sparse_attn_fwd), and dP_ij = <dO[b,h,i,:], V[b,h,j,:]>:
+ *
+ *     dV[b,h,j,:] = sum_i P_ij dO[b,h,i,:]
+ *     dS_ij       = P_ij (dP_ij - sum_d dO[b,h,i,d] O[b,h,i,d])
+ *     dQ[b,h,i,:] = scale sum_j dS_ij K[b,h,j,:]        dK[b,h,j,:] = scale sum_i dS_ij Q[b,h,i,:]
+ *
+ * dK and dV are accumulated per block column of the layout, which needs the layout's transpose:
+ *
+ * ap_build_layout_transpose: for every (head, block column kb) the tiles of that column in
+ * ascending block-row order.
+ *   row_ptr, col_idx   from ap_build_layout (same H, Lq, Lk, block_m, block_n, cap)
+ *   col_ptr       out, int32 [H * ceil(Lk/block_n) + 1]: tiles of column c are
+ *                 [col_ptr[c], col_ptr[c+1])
+ *   row_idx       out, int32 [cap]: block row qb of each of them
+ *   tile_idx      out, int32 [cap]: its position in col_idx / bitmaps
+ *   A truncated layout (more tiles than cap) must not be transposed.  Three launches, deterministic.
+ *
+ * ap_sparse_attn_bwd:
+ *   Q, K, V, O, dO, lse   the forward call's inputs and outputs and the gradient of O; O and dO
+ *                 share stride_o, dQ shares stride_q, dK stride_k, dV stride_v (all as in
+ *                 ap_sparse_attn_fwd); lse float [B, H, Lq] contiguous (required)
+ *   dQ, dK, dV    out; every element is written (zeros where nothing contributes); must not
+ *                 alias any input
+ *   workspace     device scratch of at least ap_bwd_workspace_bytes(B, H, Lq) bytes, 16-byte
+ *                 aligned (the row sums of dO * O)
+ *
+ * Supported: dtype = AP_BF16, D in {32, 64, 128}, block_m = block_n = 64.  Three launches.
+ * Deterministic (no floating-point atomics): dQ is formed per block row, dK and dV per block
+ * column, each recomputing the scores of its tiles.
+ * ------------------------------------------------------------------------------------------- */
+ap_status ap_build_layout_transpose(const int32_t *row_ptr, const int32_t *col_idx, int H, int Lq,
+                                    int Lk, int block_m, int block_n, int64_t cap, int32_t *col_ptr,
+                                    int32_t *row_idx, int32_t *tile_idx, void *stream);
+
+size_t ap_bwd_workspace_bytes(int B, int H, int Lq);
+
+ap_status ap_sparse_attn_bwd(const void *Q, const void *K, const void *V, const void *O,
+                             const void *dO, const float *lse, void *dQ, void *dK, void *dV,
+                             ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                             const int64_t *stride_q, const int64_t *stride_k,
+                             const int64_t *stride_v, const int64_t *stride_o,
+                             const int32_t *row_ptr, const int32_t *col_idx,
+                             const uint64_t *bitmaps, const int32_t *col_ptr,
+                             const int32_t *row_idx, const int32_t *tile_idx, int block_m,
+                             int block_n, int causal, float softmax_scale, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Mask construction, step 1: accumulate attention matrices into the mean map (Section 3.2,
  * Eq. (1)).
  *

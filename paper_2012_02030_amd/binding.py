@@ -26,6 +26,7 @@ AP_BF16 = 1
 
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
            "ap_build_layout", "ap_build_schedule", "ap_sparse_attn_fwd",
+           "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
            "ap_attention_maps_workspace_bytes", "ap_accumulate_attention_maps",
            "ap_prune_mask_workspace_bytes", "ap_prune_mask")
 
@@ -73,6 +74,13 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(i64), ctypes.POINTER(i64),
                                          vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
                                          ctypes.c_float, vp]
+        L.ap_build_layout_transpose.restype = i32
+        L.ap_build_layout_transpose.argtypes = [vp, vp, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
+        L.ap_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.ap_bwd_workspace_bytes.argtypes = [i32] * 3
+        L.ap_sparse_attn_bwd.restype = i32
+        L.ap_sparse_attn_bwd.argtypes = [vp] * 9 + [i32] * 6 + [ctypes.POINTER(i64)] * 4 + [vp] * 6 + \
+                                        [i32, i32, i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
         L.ap_attention_maps_workspace_bytes.restype = ctypes.c_size_t
         L.ap_attention_maps_workspace_bytes.argtypes = [i32] * 3
         L.ap_accumulate_attention_maps.restype = i32
@@ -243,6 +251,74 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_fwd")
     return out, lse
+
+
+class LayoutT(NamedTuple):
+    """Transpose of a layout: the tiles of every (head, block column), ascending block rows."""
+    col_ptr: torch.Tensor    # int32 [H*nKB + 1]
+    row_idx: torch.Tensor    # int32 [cap]
+    tile_idx: torch.Tensor   # int32 [cap]
+
+
+def ap_build_layout_transpose(layout: Layout, stream: Optional[torch.cuda.Stream] = None) -> LayoutT:
+    """Asynchronous on the stream; the layout must not be truncated."""
+    dev = layout.row_ptr.device
+    cap = int(layout.col_idx.shape[0])
+    nkb = -(-layout.Lk // layout.block_n)
+    lt = LayoutT(torch.empty(layout.H * nkb + 1, dtype=torch.int32, device=dev),
+                 torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
+                 torch.empty(max(cap, 1), dtype=torch.int32, device=dev))
+    st = lib().ap_build_layout_transpose(layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.H,
+                                         layout.Lq, layout.Lk, layout.block_m, layout.block_n, cap,
+                                         lt.col_ptr.data_ptr(), lt.row_idx.data_ptr(),
+                                         lt.tile_idx.data_ptr(), _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_build_layout_transpose")
+    return lt
+
+
+def ap_bwd_workspace_bytes(B: int, H: int, Lq: int) -> int:
+    return int(lib().ap_bwd_workspace_bytes(B, H, Lq))
+
+
+def ap_sparse_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: torch.Tensor,
+                       dO: torch.Tensor, lse: torch.Tensor, layout: Layout, layout_t: LayoutT,
+                       causal: bool = False, softmax_scale: float = 0.0,
+                       stream: Optional[torch.cuda.Stream] = None):
+    """Gradients (dQ, dK, dV) of ap_sparse_attn_fwd's O with respect to Q, K, V (bf16).
+
+    O and lse are the forward call's outputs; dO must have O's strides.  Asynchronous on the stream."""
+    for t in (Q, K, V, O, dO):
+        if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1:
+            raise ValueError("Q, K, V, O, dO must be bfloat16 [B, H, L, D] with a contiguous last dimension")
+    B, H, Lq, D = Q.shape
+    Lk = K.shape[2]
+    if tuple(K.shape) != (B, H, Lk, D) or tuple(V.shape) != (B, H, Lk, D) or \
+            tuple(O.shape) != (B, H, Lq, D) or tuple(dO.shape) != (B, H, Lq, D):
+        raise ValueError("shape mismatch")
+    if (H, Lq, Lk) != (layout.H, layout.Lq, layout.Lk):
+        raise ValueError("layout was built for other sizes")
+    if dO.stride() != O.stride():
+        dO = dO.contiguous() if O.is_contiguous() else dO.clone(memory_format=torch.preserve_format)
+        if dO.stride() != O.stride():
+            raise ValueError("dO must have O's strides")
+    lse = lse.contiguous()
+    dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    dK = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device)
+    dV = torch.empty_strided(V.shape, V.stride(), dtype=V.dtype, device=V.device)
+    ws_bytes = ap_bwd_workspace_bytes(B, H, Lq)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=Q.device)
+    st = lib().ap_sparse_attn_bwd(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), lse.data_ptr(),
+        dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), AP_BF16, B, H, Lq, Lk, D,
+        _strides3(Q), _strides3(K), _strides3(V), _strides3(O),
+        layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
+        layout_t.col_ptr.data_ptr(), layout_t.row_idx.data_ptr(), layout_t.tile_idx.data_ptr(),
+        layout.block_m, layout.block_n, int(bool(causal)), float(softmax_scale), ws.data_ptr(),
+        ws_bytes, _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_sparse_attn_bwd")
+    return dQ, dK, dV
 
 
 def ap_attention_maps_workspace_bytes(B: int, H: int, Lq: int) -> int:

@@ -156,6 +156,85 @@ ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* 
     return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
+ap_status ap_build_layout_transpose(const int32_t* row_ptr, const int32_t* col_idx, int H, int Lq,
+                                    int Lk, int block_m, int block_n, int64_t cap, int32_t* col_ptr,
+                                    int32_t* row_idx, int32_t* tile_idx, void* stream)
+{
+    if (!row_ptr || !col_idx || !col_ptr || !row_idx || !tile_idx) return AP_ERR_INVALID_ARG;
+    if (H <= 0 || Lq <= 0 || Lk <= 0 || cap < 0) return AP_ERR_INVALID_ARG;
+    if (!ap::layout_shape_ok(H, Lq, Lk, block_m, block_n)) return AP_ERR_UNSUPPORTED;
+    if (!aligned(row_ptr, 4) || !aligned(col_idx, 4) || !aligned(col_ptr, 4) || !aligned(row_idx, 4) ||
+        !aligned(tile_idx, 4))
+        return AP_ERR_INVALID_ARG;
+    const int nQB = (Lq + block_m - 1) / block_m, nKB = (Lk + block_n - 1) / block_n;
+    return ap::launch_layout_transpose(row_ptr, col_idx, H, nQB, nKB, cap, col_ptr, row_idx, tile_idx,
+                                       (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+size_t ap_bwd_workspace_bytes(int B, int H, int Lq)
+{
+    if (B <= 0 || H <= 0 || Lq <= 0) return 0;
+    return (size_t)B * (size_t)H * (size_t)Lq * sizeof(float);
+}
+
+ap_status ap_sparse_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
+                             const void* dO, const float* lse, void* dQ, void* dK, void* dV,
+                             ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                             const int64_t* stride_q, const int64_t* stride_k,
+                             const int64_t* stride_v, const int64_t* stride_o,
+                             const int32_t* row_ptr, const int32_t* col_idx,
+                             const uint64_t* bitmaps, const int32_t* col_ptr,
+                             const int32_t* row_idx, const int32_t* tile_idx, int block_m,
+                             int block_n, int causal, float softmax_scale, void* workspace,
+                             size_t workspace_bytes, void* stream)
+{
+    if (!Q || !K || !V || !O || !dO || !lse || !dQ || !dK || !dV || !stride_q || !stride_k ||
+        !stride_v || !stride_o || !row_ptr || !col_idx || !bitmaps || !col_ptr || !row_idx ||
+        !tile_idx || !workspace)
+        return AP_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || Lq <= 0 || Lk <= 0 || D <= 0 || block_m <= 0 || block_n <= 0)
+        return AP_ERR_INVALID_ARG;
+    if (dtype != AP_F32 && dtype != AP_BF16) return AP_ERR_INVALID_ARG;
+    if (causal && Lk < Lq) return AP_ERR_INVALID_ARG;
+    if (isnan(softmax_scale) || isinf(softmax_scale)) return AP_ERR_INVALID_ARG;
+    const void* ins[5] = {Q, K, V, O, dO};
+    for (const void* in : ins)
+        if (dQ == in || dK == in || dV == in) return AP_ERR_INVALID_ARG;
+    if (dQ == dK || dQ == dV || dK == dV) return AP_ERR_INVALID_ARG;
+    if (dtype != AP_BF16) return AP_ERR_UNSUPPORTED;
+    if (!(D == 32 || D == 64 || D == 128)) return AP_ERR_UNSUPPORTED;
+    if (block_m != 64 || block_n != 64) return AP_ERR_UNSUPPORTED;
+    const long long nQB = (Lq + 63) / 64, nKB = (Lk + 63) / 64;
+    if (nQB * H * B >= 2147483647LL || nKB * H * B >= 2147483647LL) return AP_ERR_UNSUPPORTED;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16) || !aligned(dO, 16) ||
+        !aligned(dQ, 16) || !aligned(dK, 16) || !aligned(dV, 16) || !aligned(lse, 4) ||
+        !aligned(row_ptr, 4) || !aligned(col_idx, 4) || !aligned(bitmaps, 8) || !aligned(col_ptr, 4) ||
+        !aligned(row_idx, 4) || !aligned(tile_idx, 4) || !aligned(workspace, 16))
+        return AP_ERR_INVALID_ARG;
+    if (!strides_ok(stride_q, D, 8) || !strides_ok(stride_k, D, 8) || !strides_ok(stride_v, D, 8) ||
+        !strides_ok(stride_o, D, 8))
+        return AP_ERR_INVALID_ARG;
+    // tiles of every operand are addressed with 32-bit byte offsets inside a (batch, head) slice
+    if ((long long)Lk * stride_k[2] * 2 >= 2147483647LL || (long long)Lk * stride_v[2] * 2 >= 2147483647LL ||
+        (long long)Lq * stride_q[2] * 2 >= 2147483647LL || (long long)Lq * stride_o[2] * 2 >= 2147483647LL)
+        return AP_ERR_UNSUPPORTED;
+    if (workspace_bytes < ap_bwd_workspace_bytes(B, H, Lq)) return AP_ERR_CAPACITY;
+
+    ap::BwdArgs a;
+    a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.lse = lse;
+    a.dQ = dQ; a.dK = dK; a.dV = dV;
+    a.B = B; a.H = H; a.Lq = Lq; a.Lk = Lk; a.D = D;
+    for (int k = 0; k < 3; ++k) {
+        a.sq[k] = stride_q[k]; a.sk[k] = stride_k[k]; a.sv[k] = stride_v[k]; a.so[k] = stride_o[k];
+    }
+    a.row_ptr = row_ptr; a.col_idx = col_idx; a.bitmaps = bitmaps;
+    a.col_ptr = col_ptr; a.row_idx = row_idx; a.tile_idx = tile_idx;
+    a.causal = causal ? 1 : 0;
+    a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+    a.delta = (float*)workspace;
+    return ap::launch_bwd(a, (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
 size_t ap_attention_maps_workspace_bytes(int B, int H, int Lq)
 {
     if (B <= 0 || H <= 0 || Lq <= 0) return 0;

@@ -50,6 +50,34 @@ hipError_t launch_fwd_valu(const FwdArgs& a, bool bf16, hipStream_t stream);
 // bf16 matrix-core kernel; block_m 64 or 128, block_n 64
 hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream);
 
+// ---- backward pass (ap_layout_transpose.hip, ap_attn_bwd.hip)
+hipError_t launch_layout_transpose(const int32_t* row_ptr, const int32_t* col_idx, int H, int nQB,
+                                   int nKB, long long cap, int32_t* col_ptr, int32_t* row_idx,
+                                   int32_t* tile_idx, hipStream_t stream);
+struct BwdArgs {
+    const void* Q;
+    const void* K;
+    const void* V;
+    const void* O;
+    const void* dO;
+    const float* lse;
+    void* dQ;
+    void* dK;
+    void* dV;
+    int B, H, Lq, Lk, D;
+    long long sq[3], sk[3], sv[3], so[3];   // element strides: batch, head, sequence
+    const int32_t* row_ptr;
+    const int32_t* col_idx;
+    const uint64_t* bitmaps;
+    const int32_t* col_ptr;
+    const int32_t* row_idx;
+    const int32_t* tile_idx;
+    int causal;
+    float scale;                    // already resolved (> 0)
+    float* delta;                   // [B, H, Lq] scratch: sum_d dO * O of each row
+};
+hipError_t launch_bwd(const BwdArgs& a, hipStream_t stream);
+
 // ---- mask construction: mean attention map (ap_maps.hip)
 struct MapArgs {
     const void* Q;

@@ -25,61 +25,6 @@ namespace {
 
 using namespace mfma;
 
-// S^T of one 64-key tile held in LDS (swizzled rows of D bf16) against the Q^T operand in
-// registers; n = query inside the wavefront, k_swz = (lane / 32) ^ swz_k(n).
-template <int D>
-__device__ __forceinline__ void qk_64(const uint16_t* Ks, const bf16x8* qreg, int n, int k_swz,
-                                      f32x16* sacc)
-{
-    constexpr int KSTEPS = D / 16;
-    constexpr int AHEAD = KSTEPS < 3 ? KSTEPS : 3;           // key operands requested this many steps early
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
-    bf16x8 kreg[KSTEPS][2];
-    auto read_step = [&](int kk) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-            kreg[kk][kb] = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + n) * D + ((2 * kk) ^ k_swz) * 8);
-    };
-#pragma unroll
-    for (int kk = 0; kk < AHEAD; ++kk) read_step(kk);
-#pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) {
-        if (kk + AHEAD < KSTEPS) read_step(kk + AHEAD);
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-            sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk][kb], qreg[kk], sacc[kb], 0, 0, 0);
-    }
-    // pin that order, so that LDS latency is paid once per tile and not once per step
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 * AHEAD, 0);
-#pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) {
-        if (kk + AHEAD < KSTEPS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-    }
-}
-
-// Makes the compiler place its own wait for these loaded registers here (right after a
-// wait_vmem(), where it costs nothing) instead of in front of their first real use, where it
-// would also wait for the tile loads issued in between.
-template <int N>
-__device__ __forceinline__ void settle(bf16x8* q)
-{
-#pragma unroll
-    for (int kk = 0; kk < N; ++kk) asm volatile("" : "+v"(q[kk]));
-}
-
-// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  This bijection gives
-// every XCD one contiguous range of the linear workgroup index, so that the workgroups that
-// share the K and Q rows of a head (and example) also share an L2.
-__device__ __forceinline__ int xcd_contiguous(int bid, int grid)
-{
-    const int x = bid & 7, q = grid >> 3, r = grid & 7;
-    return x * q + min(x, r) + (bid >> 3);
-}
-
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW) void row_lse_kernel(MapArgs a, int nQB)
 {

@@ -108,5 +108,141 @@ __device__ __forceinline__ void issue_gather_loads(rsrc_t rsrc, lds_u16* dst, co
     }
 }
 
+// C[64 x 32] = T[64 x D] * R^T[D x 32]: T is a 64-row tile in LDS (rows of D bf16, key swizzle),
+// R^T the operand this wavefront keeps in registers (lane l: row l % 32 of R, elements
+// 16*kk + 8*(l/32) .. +7).  Result in the matrix-core layout: lane l holds column l % 32 and,
+// of each 32-row block, rows 8*(i/4) + 4*(l/32) + i%4.  n = l % 32, k_swz = (l / 32) ^ swz_k(n).
+template <int D>
+__device__ __forceinline__ void qk_64(const uint16_t* Ks, const bf16x8* qreg, int n, int k_swz,
+                                      f32x16* sacc)
+{
+    constexpr int KSTEPS = D / 16;
+    constexpr int AHEAD = KSTEPS < 3 ? KSTEPS : 3;           // key operands requested this many steps early
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+    bf16x8 kreg[KSTEPS][2];
+    auto read_step = [&](int kk) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+            kreg[kk][kb] = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + n) * D + ((2 * kk) ^ k_swz) * 8);
+    };
+#pragma unroll
+    for (int kk = 0; kk < AHEAD; ++kk) read_step(kk);
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        if (kk + AHEAD < KSTEPS) read_step(kk + AHEAD);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+            sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[kk][kb], qreg[kk], sacc[kb], 0, 0, 0);
+    }
+    // pin that order, so that LDS latency is paid once per tile and not once per step
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * AHEAD, 0);
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+        if (kk + AHEAD < KSTEPS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    }
+}
+
+// Makes the compiler place its own wait for these loaded registers here (right after a
+// wait_vmem(), where it costs nothing) instead of in front of their first real use, where it
+// would also wait for the tile loads issued in between.
+template <int N>
+__device__ __forceinline__ void settle(bf16x8* q)
+{
+#pragma unroll
+    for (int kk = 0; kk < N; ++kk) asm volatile("" : "+v"(q[kk]));
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  This bijection gives
+// every XCD one contiguous range of the linear workgroup index, so that the workgroups that
+// share the K and Q rows of a head (and example) also share an L2.
+__device__ __forceinline__ int xcd_contiguous(int bid, int grid)
+{
+    const int x = bid & 7, q = grid >> 3, r = grid & 7;
+    return x * q + min(x, r) + (bid >> 3);
+}
+
+// Per-lane constants of the transposing LDS reads of a 64-row tile stored with the value swizzle.
+struct TrRead {
+    int lane_row, in_chunk, chunk_lo, swz;
+};
+template <int D>
+__device__ __forceinline__ TrRead make_tr_read(int lane)
+{
+    const int hh = lane >> 5, i16 = lane & 15, g = (lane >> 4) & 1, vj = i16 >> 2;
+    TrRead t;
+    t.lane_row = 4 * hh + vj;
+    t.in_chunk = 4 * (i16 & 1);
+    t.chunk_lo = 2 * g + ((i16 >> 1) & 1);
+    t.swz = swz_v<D>(vj) >> 2;                               // xor on the 4-chunk group index
+    return t;
+}
+
+// acc^T[D x 32] += T^T[D x 64] * P[64 x 32]: T is a 64-row tile in LDS (value swizzle), read with
+// the transposing load; P is held in the layout qk_64 produces (fp32, rounded to bf16 here).
+// The operands of 16-row step ks + 1 are requested before the matrix instructions of step ks.
+template <int D>
+__device__ __forceinline__ void tr_mm_64(lds_u16* Ts, const f32x16* p, f32x16* acc, const TrRead& t)
+{
+    constexpr int DBLK = D / 32;
+    auto read_t = [&](int ks, bf16x8* treg) {
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) {
+            const int chunk = ((db ^ t.swz) << 2) + t.chunk_lo;
+            lds_u16* p0 = Ts + (16 * ks + t.lane_row) * D + chunk * 8 + t.in_chunk;
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p0);
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * D));
+            treg[db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    };
+    bf16x8 tcur[DBLK], tnext[DBLK];
+    read_t(0, tcur);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)p[ks >> 1][8 * (ks & 1) + e];
+        if (ks + 1 < 4) read_t(ks + 1, tnext);
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db)
+            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur[db], pb, acc[db], 0, 0, 0);
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) tcur[db] = tnext[db];
+    }
+}
+
+// Write acc^T[D x 32] * mul as 32 bf16 rows of D elements: staged through this wavefront's own
+// 32 x D region of LDS (key swizzle), then 128-bit stores; rows >= rows_valid are dropped.
+template <int D>
+__device__ __forceinline__ void store_rows_bf16(uint16_t* stage, const f32x16* acc, float mul, int lane,
+                                                uint16_t* dst, long long row_stride, int rows_valid)
+{
+    constexpr int DBLK = D / 32, CPR = D / 8;
+    const int n = lane & 31, hh = lane >> 5;
+    const int f = swz_k<D>(n);
+#pragma unroll
+    for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            uint2 w;
+            w.x = pack_bf16_rne(acc[db][4 * g4] * mul, acc[db][4 * g4 + 1] * mul);
+            w.y = pack_bf16_rne(acc[db][4 * g4 + 2] * mul, acc[db][4 * g4 + 3] * mul);
+            const int chunk = (4 * db + g4) ^ f;
+            *reinterpret_cast<uint2*>(stage + n * D + chunk * 8 + 4 * hh) = w;
+        }
+    // the same wavefront reads back what it wrote: no barrier needed, only LDS ordering
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int u = 0; u < (32 * CPR) / 64; ++u) {
+        const int idx = u * 64 + lane;
+        const int rr = idx / CPR, c = idx % CPR;
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + rr * D + (c ^ swz_k<D>(rr)) * 8);
+        if (rr < rows_valid) *reinterpret_cast<uint4*>(dst + (size_t)rr * row_stride + c * 8) = v;
+    }
+}
+
 }  // namespace mfma
 }  // namespace ap

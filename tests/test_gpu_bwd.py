@@ -1,0 +1,114 @@
+"""GPU parity of the backward pass (gradients of the masked-attention equation of Section 3.2)
+against the fp64 oracle, and of the transposed layout against its definition.
+
+Tolerance: gradients are sums of up to Lk (dQ) or Lq (dK, dV) products whose factors P and dS are
+rounded to bf16 (relative 2^-9) before the matrix-core product, the result is rounded to bf16
+once more, and delta uses the bf16 O of the forward pass.  With O(1) inputs that gives errors of
+a few 1e-3 of the largest gradient entry; the bar is max-abs error <= 2e-2 * max(1, max|oracle|),
+the forward pass's 2e-2 scaled to the gradient's magnitude.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2012_02030_amd import binding as ap
+from paper_2012_02030_amd import synth
+
+from gpu_util import to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def transpose_reference(row_ptr, col_idx, H, nQB, nKB):
+    cols = [[] for _ in range(H * nKB)]
+    for r in range(H * nQB):
+        h, qb = divmod(r, nQB)
+        for t in range(row_ptr[r], row_ptr[r + 1]):
+            cols[h * nKB + col_idx[t]].append((qb, t))
+    col_ptr = np.zeros(H * nKB + 1, dtype=np.int32)
+    row_idx, tile_idx = [], []
+    for c, lst in enumerate(cols):
+        col_ptr[c + 1] = col_ptr[c] + len(lst)
+        row_idx += [q for q, _ in lst]
+        tile_idx += [t for _, t in lst]
+    return col_ptr, np.array(row_idx, dtype=np.int32), np.array(tile_idx, dtype=np.int32)
+
+
+@pytest.mark.parametrize("shape", [(2, 64, 64, 0.5), (3, 200, 330, 0.02), (1, 1000, 70, 0.3), (2, 130, 130, 0.0)])
+def test_layout_transpose_matches_definition(shape):
+    H, Lq, Lk, density = shape
+    mask = synth.random_mask(H, Lq, Lk, density, seed=Lq)
+    lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
+    lt = ap.ap_build_layout_transpose(lay)
+    torch.cuda.synchronize()
+    rp, ci, _ = oracle.build_layout(mask, 64, 64)
+    nQB, nKB = -(-Lq // 64), -(-Lk // 64)
+    col_ptr, row_idx, tile_idx = transpose_reference(rp, ci, H, nQB, nKB)
+    nnz = len(ci)
+    assert np.array_equal(lt.col_ptr.cpu().numpy(), col_ptr)
+    assert np.array_equal(lt.row_idx[:nnz].cpu().numpy(), row_idx)
+    assert np.array_equal(lt.tile_idx[:nnz].cpu().numpy(), tile_idx)
+
+
+def run_bwd(Q, K, V, dO, mask_np, causal, scale=0.0):
+    dq, rq = to_device(Q, "bf16")
+    dk, rk = to_device(K, "bf16")
+    dv, rv = to_device(V, "bf16")
+    dg, rg = to_device(dO, "bf16")
+    lay = ap.ap_build_layout(torch.from_numpy(mask_np).cuda(), 64, 64)
+    lt = ap.ap_build_layout_transpose(lay)
+    O, lse = ap.ap_sparse_attn_fwd(dq, dk, dv, lay, causal=causal, softmax_scale=scale)
+    gQ, gK, gV = ap.ap_sparse_attn_bwd(dq, dk, dv, O, dg, lse, lay, lt, causal=causal, softmax_scale=scale)
+    torch.cuda.synchronize()
+    ref = oracle.masked_attention_backward(rq, rk, rv, mask_np, rg, causal=causal, scale=scale)
+    errs = []
+    for name, got, want in zip(("dQ", "dK", "dV"), (gQ, gK, gV), ref):
+        g = got.double().cpu().numpy()
+        assert np.isfinite(g).all(), name + " has non-finite entries"
+        tol = 2e-2 * max(1.0, float(np.abs(want).max()))
+        err = float(np.abs(g - want).max())
+        assert err <= tol, "max |%s - oracle| = %.3e > %.3e" % (name, err, tol)
+        errs.append(err)
+    return errs
+
+
+def rand_inputs(seed, B, H, Lq, Lk, D):
+    rng = np.random.default_rng([synth.SEED, 4242, seed])
+    return tuple(rng.standard_normal(s, dtype=np.float32) for s in
+                 ((B, H, Lq, D), (B, H, Lk, D), (B, H, Lk, D), (B, H, Lq, D)))
+
+
+BWD_CASES = [
+    # B, H, Lq, Lk, D, causal, density
+    (2, 3, 128, 128, 64, False, 0.5),
+    (1, 2, 200, 200, 64, True, 0.3),
+    (2, 2, 100, 157, 32, False, 0.3),
+    (1, 2, 100, 300, 128, True, 0.2),
+    (1, 1, 192, 192, 128, False, 1.0),       # nothing pruned: ordinary attention
+    (1, 2, 64, 64, 64, True, 0.05),          # very sparse: empty rows and columns
+    (1, 1, 1, 1, 32, False, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", BWD_CASES, ids=lambda c: "B%d_H%d_%dx%d_D%d_%s_%g" % (c[:5] + ("causal" if c[5] else "full", c[6])))
+def test_backward_matches_oracle(case):
+    B, H, Lq, Lk, D, causal, density = case
+    Q, K, V, dO = rand_inputs(Lq + Lk + D, B, H, Lq, Lk, D)
+    mask = synth.random_mask(H, Lq, Lk, density, seed=D + Lq)
+    run_bwd(Q, K, V, dO, mask, causal)
+
+
+def test_backward_on_the_structured_masks():
+    """C3's band-plus-spikes causal mask (two heads of it) and C2's noisy non-causal one."""
+    for name, heads, batch in (("C3", 2, 1), ("C2", 3, 2)):
+        cfg = synth.CONFIGS[name]
+        mask = np.stack([synth.head_mask(cfg, h) for h in range(heads)]).astype(np.uint8)
+        Q, K, V, dO = rand_inputs(7, batch, heads, cfg.Lq, cfg.Lk, cfg.D)
+        run_bwd(Q, K, V, dO, mask, cfg.causal)
+
+
+def test_backward_explicit_scale_and_large_scores():
+    Q, K, V, dO = rand_inputs(9, 1, 2, 128, 128, 64)
+    mask = synth.random_mask(2, 128, 128, 0.4, seed=3)
+    run_bwd(2.0 * Q, 2.0 * K, V, dO, mask, False, scale=0.2)
