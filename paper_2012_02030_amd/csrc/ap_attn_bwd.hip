@@ -121,8 +121,10 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a, int nQB)
 
     const int r = h * nQB + qb;
     const int t0 = a.row_ptr[r], t1 = a.row_ptr[r + 1];
+    const long long block_diag = (long long)qb * 64 + 63 + ((long long)a.Lk - a.Lq);
     for (int t = t0; t < t1; ++t) {
         const int k0 = a.col_idx[t] * kBN;
+        if (a.causal && k0 > block_diag) break;              // columns ascend: the rest is hidden too
         __syncthreads();                                     // the previous tile is consumed
         issue_tile_loads<D, 2, false>(k_rsrc, Kk, k0, sk_bytes, wave, lane);
         issue_tile_loads<D, 2, true>(k_rsrc, Kv, k0, sk_bytes, wave, lane);
@@ -224,6 +226,7 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_kernel(BwdArgs a, int nQB, int
         const int qb = a.row_idx[ci];
         const int t = a.tile_idx[ci];
         const int q0 = qb * 64;
+        if (a.causal && (long long)kb * 64 > (long long)q0 + 63 + off) continue;   // hidden from every row of the tile
         __syncthreads();                                     // the previous tile is consumed
         issue_tile_loads<D, 2, false>(q_rsrc, Qk, q0, sq_bytes, wave, lane);
         issue_tile_loads<D, 2, true>(q_rsrc, Qv, q0, sq_bytes, wave, lane);

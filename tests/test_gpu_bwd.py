@@ -112,3 +112,27 @@ def test_backward_explicit_scale_and_large_scores():
     Q, K, V, dO = rand_inputs(9, 1, 2, 128, 128, 64)
     mask = synth.random_mask(2, 128, 128, 0.4, seed=3)
     run_bwd(2.0 * Q, 2.0 * K, V, dO, mask, False, scale=0.2)
+
+
+def test_backward_full_size_c5_two_slices_against_oracle():
+    """The benchmark's shape and launch configuration (B4 H16 L4096 D128 causal, C5's mask); the
+    gradients of two (example, head) slices are compared element by element."""
+    cfg = synth.CONFIGS["C5"]
+    mask = synth.make_mask(cfg)
+    Q, K, V = synth.make_qkv(cfg)
+    dO = np.random.default_rng([synth.SEED, 4243]).standard_normal(Q.shape, dtype=np.float32)
+    dq, dk, dv, dg = (torch.from_numpy(x).to(torch.bfloat16).cuda() for x in (Q, K, V, dO))
+    lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
+    lt = ap.ap_build_layout_transpose(lay)
+    O, lse = ap.ap_sparse_attn_fwd(dq, dk, dv, lay, causal=True)
+    gQ, gK, gV = ap.ap_sparse_attn_bwd(dq, dk, dv, O, dg, lse, lay, lt, causal=True)
+    torch.cuda.synchronize()
+    for t in (gQ, gK, gV):
+        assert bool(torch.isfinite(t).all())
+    for b, h in ((0, 0), (3, 11)):
+        sl = lambda t: t[b:b + 1, h:h + 1].double().cpu().numpy()
+        ref = oracle.masked_attention_backward(sl(dq), sl(dk), sl(dv), mask[h:h + 1], sl(dg), causal=True)
+        for name, got, want in zip(("dQ", "dK", "dV"), (gQ, gK, gV), ref):
+            err = float(np.abs(sl(got) - want).max())
+            tol = 2e-2 * max(1.0, float(np.abs(want).max()))
+            assert err <= tol, "%s[%d,%d]: %.3e > %.3e" % (name, b, h, err, tol)
