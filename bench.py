@@ -39,6 +39,9 @@ def parse():
     p.add_argument("--no-sched", action="store_true", help="walk the layout itself instead of the visit schedule")
     p.add_argument("--only", action="store_true", help="skip the per-config table and the CPU baseline")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    p.add_argument("--only-backward", action="store_true",
+                   help="time only the backward pass at the workload's shape and print its figures")
+    p.add_argument("--no-backward", action="store_true", help="skip the timing of the backward pass")
     p.add_argument("--only-mask-construction", action="store_true",
                    help="time only the mask-construction kernels at the workload's shape and print their figures")
     p.add_argument("--no-mask-construction", action="store_true",
@@ -306,6 +309,54 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
+    def run_backward(cfg, mask_np, steps):
+        """Forward + backward of cfg under its AP mask (plain layout walk, block 64x64)."""
+        if cfg.dtype != "bf16":
+            return None
+        lay = ap.ap_build_layout(torch.from_numpy(mask_np).to(dev), 64, 64)
+        lt = ap.ap_build_layout_transpose(lay)
+        q, k, v = (torch.from_numpy(x).to(torch.bfloat16).to(dev) for x in synth.make_qkv(cfg))
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(synth.SEED + 77)
+        g = torch.randn(q.shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        O, lse = ap.ap_sparse_attn_fwd(q, k, v, lay, causal=cfg.causal)
+
+        def timed(fn, n):
+            fn()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            torch.cuda.synchronize()
+            evs[0].record()
+            for i in range(n):
+                fn()
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            return float(np.mean([evs[i].elapsed_time(evs[i + 1]) for i in range(n)]))
+
+        bwd_ms = timed(lambda: ap.ap_sparse_attn_bwd(q, k, v, O, g, lse, lay, lt, causal=cfg.causal), steps)
+        tr_ms = timed(lambda: ap.ap_build_layout_transpose(lay), steps)
+        kept = int(mask_np.sum())
+        kept_flop = 10.0 * cfg.D * kept * cfg.B               # five N^2-sized products per kept entry
+        tiles = int(lay.nnz.item())
+        tile_flop = 10.0 * cfg.D * 64 * 64 * tiles * cfg.B
+        es = 2
+        alg = es * cfg.B * cfg.H * cfg.D * (4 * cfg.Lq + 4 * cfg.Lk) + 4 * cfg.B * cfg.H * cfg.Lq
+        return {
+            "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D, "causal": cfg.causal},
+            "tiles_visited": tiles,
+            "bwd_ms": bwd_ms,
+            "kept_tflops": kept_flop / (bwd_ms * 1e-3) / 1e12,
+            "tile_mfma_tflops": tile_flop / (bwd_ms * 1e-3) / 1e12,
+            "tile_mfma_frac": tile_flop / (bwd_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "hbm_alg_bytes": alg,
+            "hbm_gbs": alg / (bwd_ms * 1e-3) / 1e9,
+            "layout_transpose_ms": tr_ms,
+        }
+
+    if args.only_backward:
+        cfg = synth.CONFIGS[args.workload]
+        print(json.dumps({"backward": run_backward(cfg, synth.make_mask(cfg), args.steps)}), flush=True)
+        return
+
     if args.only_mask_construction:
         print(json.dumps({"mask_construction": run_mask_construction(synth.CONFIGS[args.workload], args.steps)}),
               flush=True)
@@ -364,6 +415,12 @@ def main():
         mask_construction = run_mask_construction(head, 10)
         torch.cuda.empty_cache()
 
+    backward = None
+    if not args.only and not args.no_backward:
+        log("timing the backward pass at the", head.name, "shape ...")
+        backward = run_backward(head, head_mask, 10)
+        torch.cuda.empty_cache()
+
     out = {
         "metric": "kept-entry TFLOP/s of masked attention fwd (ms/call and speedup vs dense-mask run alongside)",
         "value": head_res["kept_tflops"],
@@ -396,6 +453,7 @@ def main():
         "cpu_baseline": cpu,
         "parity": parity,
         "mask_construction": mask_construction,
+        "backward": backward,
         "per_config": per_config,
     }
     print(json.dumps(out), flush=True)

@@ -218,6 +218,8 @@ ap_status ap_sparse_attn_bwd(const void* Q, const void* K, const void* V, const 
     if ((long long)Lk * stride_k[2] * 2 >= 2147483647LL || (long long)Lk * stride_v[2] * 2 >= 2147483647LL ||
         (long long)Lq * stride_q[2] * 2 >= 2147483647LL || (long long)Lq * stride_o[2] * 2 >= 2147483647LL)
         return AP_ERR_UNSUPPORTED;
+    // bitmap rows are fetched with 32-bit byte offsets: 512 bytes per tile
+    if (nQB * nKB * H >= (1LL << 22)) return AP_ERR_UNSUPPORTED;
     if (workspace_bytes < ap_bwd_workspace_bytes(B, H, Lq)) return AP_ERR_CAPACITY;
 
     ap::BwdArgs a;

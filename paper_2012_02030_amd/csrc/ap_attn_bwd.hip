@@ -7,12 +7,12 @@
 //
 // Three kernels, no floating-point atomics:
 //   bwd_delta_kernel   delta_i for every (example, head, query)
-//   bwd_dq_kernel      one workgroup per (example, head, block row): walks the row's tiles as the
-//                      forward kernel does (a wavefront owns 32 queries, S^T = K Q^T and
+//   bwd_dq_kernel      one workgroup per (example, head, two block rows): walks the rows' tiles as
+//                      the forward kernel does (a wavefront owns 32 queries, S^T = K Q^T and
 //                      dP^T = V dO^T on the matrix cores, lane = query), dQ^T += K^T dS^T
-//   bwd_dkv_kernel     one workgroup per (example, head, block column): walks the column's tiles
-//                      through the transposed layout with the roles swapped (a wavefront owns 32
-//                      keys, S = Q K^T and dP = dO V^T, lane = key), dV^T += dO^T P, dK^T += Q^T dS
+//   bwd_dkv_kernel     one workgroup per (example, head, two block columns): walks the columns'
+//                      tiles through the transposed layout with the roles swapped (a wavefront owns
+//                      32 keys, S = Q K^T and dP = dO V^T, lane = key), dV^T += dO^T P, dK^T += Q^T dS
 // Both tile kernels recompute the scores from Q, K and the stored log-sum-exp; the products use
 // the operand layouts, LDS swizzles and LDS-direct tile loads of the forward kernel.
 #include <hip/hip_runtime.h>
@@ -61,26 +61,59 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(BwdArgs a)
 // log-sum-exp in base 2; a row without kept keys (lse = -inf) gets +inf, so that exp2(s - lse2) = 0
 __device__ __forceinline__ float lse2_of(float lse) { return lse == -INFINITY ? INFINITY : lse * kLog2e; }
 
+// Two ascending index lists walked together: at every step the smaller head (or both, if
+// equal) is taken.  All values are wave-uniform.
+struct Merge {
+    int ia, a1, ib, b1;          // cursors and ends of the two lists
+    int key;                     // current index value (block column or block row); INT_MAX: done
+    int ta, tb;                  // positions in the lists of the current step, -1 if absent
+};
+
+__device__ __forceinline__ void merge_step(Merge& m, const int32_t* list)
+{
+    const int ca = m.ia < m.a1 ? list[m.ia] : 0x7fffffff;
+    const int cb = m.ib < m.b1 ? list[m.ib] : 0x7fffffff;
+    m.key = ca < cb ? ca : cb;
+    m.ta = (ca == m.key && ca != 0x7fffffff) ? m.ia++ : -1;
+    m.tb = (cb == m.key && cb != 0x7fffffff) ? m.ib++ : -1;
+}
+
+// One 512-byte block (64 x 8 bytes, or 128 x 4 bytes) into LDS by the first 32 lanes of a wavefront.
+__device__ __forceinline__ void dma_512(lds_u16* dst, const void* src_base, unsigned src_bytes, long long byte_off,
+                                        int lane)
+{
+    if (lane < 32) {
+        const rsrc_t rs = make_rsrc(src_base, src_bytes);
+        load16_to_lds(lds_addr_of(dst), lane * 16, rs, (int)byte_off);
+    }
+}
+
+// dQ: one workgroup per (example, head, pair of block rows); wavefronts 0,1 own the 64 queries of
+// the first block row, wavefronts 2,3 those of the second.  The tiles of both block rows are
+// walked together in ascending column order, so a K/V tile that both need is loaded once.  Two
+// LDS stages: the next tile travels while the current one is computed, one barrier per tile.
 template <int D>
-__global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a, int nQB)
+__global__ __launch_bounds__(256, 1) void bwd_dq_kernel(BwdArgs a, int nQB, int nQP)
 {
     constexpr int TILE = kBN * D;
     constexpr int KSTEPS = D / 16;
     constexpr int DBLK = D / 32;
-    __shared__ __attribute__((aligned(1024))) uint16_t smem[3 * TILE];
-    lds_u16* Kk = (lds_u16*)smem;                            // K tile, key swizzle (rows x Q^T)
-    lds_u16* Kv = Kk + TILE;                                 // K tile, value swizzle (K^T x dS^T)
-    lds_u16* Vk = Kv + TILE;                                 // V tile, key swizzle (rows x dO^T)
+    constexpr int STAGE = 3 * TILE + 512;                    // Kk, Kv, Vk, bitmap words of both block rows
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * STAGE];
+    lds_u16* lds = (lds_u16*)smem;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
+    const int half = wave >> 1;                              // which block row of the pair
 
     const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int qb = nQB - 1 - (bid % nQB);
-    const int h = (bid / nQB) % a.H;
-    const int b = bid / (nQB * a.H);
+    const int qp = nQP - 1 - (bid % nQP);                    // long causal rows first
+    const int h = (bid / nQP) % a.H;
+    const int b = bid / (nQP * a.H);
+    const int qb = 2 * qp + half;
+    const bool have_row = qb < nQB;
 
     const uint16_t* Qp = (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1];
     const uint16_t* Gp = (const uint16_t*)a.dO + (size_t)b * a.so[0] + (size_t)h * a.so[1];
@@ -91,7 +124,7 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a, int nQB)
     const rsrc_t k_rsrc = make_rsrc(Kp, (unsigned)((a.Lk - 1) * sk_bytes + D * 2));
     const rsrc_t v_rsrc = make_rsrc(Vp, (unsigned)((a.Lk - 1) * sv_bytes + D * 2));
 
-    const int brow = wave * 32 + n;
+    const int brow = (wave & 1) * 32 + n;                    // row inside the block row
     const int qrow = qb * 64 + brow;
     const bool row_ok = qrow < a.Lq;
     const int qload = row_ok ? qrow : a.Lq - 1;
@@ -106,10 +139,11 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a, int nQB)
         }
     }
     const size_t stat = ((size_t)b * a.H + h) * a.Lq + qload;
-    const float lse2 = row_ok ? lse2_of(a.lse[stat]) : INFINITY;
-    const float delta = row_ok ? a.delta[stat] : 0.f;
+    float lse2 = row_ok ? lse2_of(a.lse[stat]) : INFINITY;
+    float delta = row_ok ? a.delta[stat] : 0.f;
     const float sc = a.scale * kLog2e;
-    const long long diag = (long long)qrow + ((long long)a.Lk - a.Lq);
+    const long long off = (long long)a.Lk - a.Lq;
+    const long long diag = (long long)qrow + off;
     const int k_swz = hh ^ swz_k<D>(n);
     const TrRead tr = make_tr_read<D>(lane);
 
@@ -119,68 +153,107 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_kernel(BwdArgs a, int nQB)
 #pragma unroll
         for (int i = 0; i < 16; ++i) dqacc[db][i] = 0.f;
 
-    const int r = h * nQB + qb;
-    const int t0 = a.row_ptr[r], t1 = a.row_ptr[r + 1];
-    const long long block_diag = (long long)qb * 64 + 63 + ((long long)a.Lk - a.Lq);
-    for (int t = t0; t < t1; ++t) {
-        const int k0 = a.col_idx[t] * kBN;
-        if (a.causal && k0 > block_diag) break;              // columns ascend: the rest is hidden too
-        __syncthreads();                                     // the previous tile is consumed
-        issue_tile_loads<D, 2, false>(k_rsrc, Kk, k0, sk_bytes, wave, lane);
-        issue_tile_loads<D, 2, true>(k_rsrc, Kv, k0, sk_bytes, wave, lane);
-        issue_tile_loads<D, 2, false>(v_rsrc, Vk, k0, sv_bytes, wave, lane);
-        uint64_t word = a.bitmaps[(size_t)t * 64 + brow];
-        wait_vmem();
-        __syncthreads();
-        if (a.causal) {
-            const long long lim = diag - k0;
-            if (lim < 0) word = 0;
-            else if (lim < 63) word &= (2ull << lim) - 1ull;
-        }
-        f32x16 sacc[2], pacc[2];
-        qk_64<D>(smem, qreg, n, k_swz, sacc);                // S^T  = K Q^T
-        qk_64<D>(smem + 2 * TILE, greg, n, k_swz, pacc);     // dP^T = V dO^T
-        const uint64_t wsh = word >> (4 * hh);
-        const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int pos = 8 * (i / 4) + (i % 4);
-                const float p = ((wbits[kb] >> pos) & 1u) ? __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -lse2)) : 0.f;
-                sacc[kb][i] = p * (pacc[kb][i] - delta);     // dS^T
+    // the two tile lists; with a causal mask they end at the last column any row of the pair sees
+    const int rA = h * nQB + 2 * qp;
+    Merge m;
+    m.ia = a.row_ptr[rA];
+    m.a1 = a.row_ptr[rA + 1];
+    m.ib = m.a1;
+    m.b1 = (2 * qp + 1 < nQB) ? a.row_ptr[rA + 2] : m.a1;
+    const long long pair_diag = (long long)(2 * qp + 1) * 64 + 63 + off;
+    const unsigned words_bytes = (unsigned)m.b1 * 512u;     // never read past the pair's last tile
+
+    auto issue = [&](const Merge& x, int stage) {
+        lds_u16* base = lds + stage * STAGE;
+        const int k0 = x.key * kBN;
+        issue_tile_loads<D, 4, false>(k_rsrc, base, k0, sk_bytes, wave, lane);
+        issue_tile_loads<D, 4, true>(k_rsrc, base + TILE, k0, sk_bytes, wave, lane);
+        issue_tile_loads<D, 4, false>(v_rsrc, base + 2 * TILE, k0, sv_bytes, wave, lane);
+        if (wave == 0 && x.ta >= 0) dma_512(base + 3 * TILE, a.bitmaps, words_bytes, (long long)x.ta * 512, lane);
+        if (wave == 2 && x.tb >= 0) dma_512(base + 3 * TILE + 256, a.bitmaps, words_bytes, (long long)x.tb * 512, lane);
+    };
+    auto live = [&](const Merge& x) {                        // anything left that some row can see?
+        return x.key != 0x7fffffff && !(a.causal && (long long)x.key * kBN > pair_diag);
+    };
+
+    // first use of the loaded registers before the loop, so that no wait for them lands inside it
+    wait_vmem();
+    settle<KSTEPS>(qreg);
+    settle<KSTEPS>(greg);
+    asm volatile("" : "+v"(lse2), "+v"(delta));
+
+    Merge cur = m;
+    merge_step(cur, a.col_idx);
+    Merge nxt = cur;
+    int stage = 0;
+    if (live(cur)) issue(cur, 0);
+    while (live(cur)) {
+        merge_step(nxt, a.col_idx);
+        wait_vmem();                                         // the current tile has landed
+        __syncthreads();                                     // ... for everybody; the other stage is free
+        if (live(nxt)) issue(nxt, stage ^ 1);
+        const int t = half ? cur.tb : cur.ta;
+        const int k0 = cur.key * kBN;
+        if (have_row && t >= 0) {
+            uint16_t* base = smem + stage * STAGE;
+            uint64_t word = *reinterpret_cast<const uint64_t*>(base + 3 * TILE + half * 256 + brow * 4);
+            if (a.causal) {
+                const long long lim = diag - k0;
+                if (lim < 0) word = 0;
+                else if (lim < 63) word &= (2ull << lim) - 1ull;
             }
-        tr_mm_64<D>(Kv, sacc, dqacc, tr);                    // dQ^T += K^T dS^T
+            f32x16 sacc[2], pacc[2];
+            qk_64<D>(base, qreg, n, k_swz, sacc);            // S^T  = K Q^T
+            qk_64<D>(base + 2 * TILE, greg, n, k_swz, pacc); // dP^T = V dO^T
+            const uint64_t wsh = word >> (4 * hh);
+            const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int pos = 8 * (i / 4) + (i % 4);
+                    const float p = ((wbits[kb] >> pos) & 1u) ? __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -lse2)) : 0.f;
+                    sacc[kb][i] = p * (pacc[kb][i] - delta); // dS^T
+                }
+            tr_mm_64<D>(lds + stage * STAGE + TILE, sacc, dqacc, tr);   // dQ^T += K^T dS^T
+        }
+        cur = nxt;
+        stage ^= 1;
     }
     __syncthreads();                                         // all wavefronts are done with the tiles
-    store_rows_bf16<D>(smem + wave * 32 * D, dqacc, a.scale, lane,
-                       dQp + (size_t)(qb * 64 + wave * 32) * a.sq[2], a.sq[2], a.Lq - (qb * 64 + wave * 32));
+    if (have_row)
+        store_rows_bf16<D>(smem + wave * 32 * D, dqacc, a.scale, lane,
+                           dQp + (size_t)(qb * 64 + (wave & 1) * 32) * a.sq[2], a.sq[2],
+                           a.Lq - (qb * 64 + (wave & 1) * 32));
 }
 
+// dK, dV: one workgroup per (example, head, pair of block columns); wavefronts 0,1 own the 64 keys
+// of the first block column, wavefronts 2,3 those of the second.  The tiles of both columns are
+// walked together in ascending block-row order through the transposed layout, so a Q/dO tile
+// that both need is loaded once.  Two LDS stages, one barrier per tile.
 template <int D>
-__global__ __launch_bounds__(128, 1) void bwd_dkv_kernel(BwdArgs a, int nQB, int nKB)
+__global__ __launch_bounds__(256, 1) void bwd_dkv_kernel(BwdArgs a, int nQB, int nKB, int nKP)
 {
     constexpr int TILE = kBN * D;
     constexpr int KSTEPS = D / 16;
     constexpr int DBLK = D / 32;
-    __shared__ __attribute__((aligned(1024))) uint16_t smem[4 * TILE];
-    __shared__ __attribute__((aligned(16))) float s_lse2[64];
-    __shared__ __attribute__((aligned(16))) float s_delta[64];
-    __shared__ __attribute__((aligned(16))) uint64_t s_word[64];
-    lds_u16* Qk = (lds_u16*)smem;                            // Q tile, key swizzle   (rows x K^T)
-    lds_u16* Qv = Qk + TILE;                                 // Q tile, value swizzle (Q^T x dS)
-    lds_u16* Gk = Qv + TILE;                                 // dO tile, key swizzle  (rows x V^T)
-    lds_u16* Gv = Gk + TILE;                                 // dO tile, value swizzle (dO^T x P)
+    // Qk, Qv, dOk, dOv, then 256 B lse, 256 B delta, 512 B words of column A, 512 B words of column B
+    constexpr int STAGE = 4 * TILE + 768;
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * STAGE];
+    lds_u16* lds = (lds_u16*)smem;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
+    const int half = wave >> 1;
 
     const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int kb = bid % nKB;
-    const int h = (bid / nKB) % a.H;
-    const int b = bid / (nKB * a.H);
+    const int kp = bid % nKP;                                // early causal columns (most tiles) first
+    const int h = (bid / nKP) % a.H;
+    const int b = bid / (nKP * a.H);
+    const int kb = 2 * kp + half;
+    const bool have_col = kb < nKB;
 
     const uint16_t* Qp = (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1];
     const uint16_t* Gp = (const uint16_t*)a.dO + (size_t)b * a.so[0] + (size_t)h * a.so[1];
@@ -191,8 +264,10 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_kernel(BwdArgs a, int nQB, int
     const int sq_bytes = (int)a.sq[2] * 2, so_bytes = (int)a.so[2] * 2;
     const rsrc_t q_rsrc = make_rsrc(Qp, (unsigned)((a.Lq - 1) * sq_bytes + D * 2));
     const rsrc_t g_rsrc = make_rsrc(Gp, (unsigned)((a.Lq - 1) * so_bytes + D * 2));
+    const size_t stat_base = ((size_t)b * a.H + h) * a.Lq;
+    const unsigned stat_bytes = (unsigned)a.Lq * 4u;         // rows >= Lq read as zeros
 
-    const int key = kb * 64 + wave * 32 + n;
+    const int key = kb * 64 + (wave & 1) * 32 + n;
     const int kload = key < a.Lk ? key : a.Lk - 1;
     bf16x8 kreg[KSTEPS], vreg[KSTEPS];                       // K^T and V^T operands
     {
@@ -208,7 +283,7 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_kernel(BwdArgs a, int nQB, int
     const long long off = (long long)a.Lk - a.Lq;
     const int k_swz = hh ^ swz_k<D>(n);
     const TrRead tr = make_tr_read<D>(lane);
-    const int kcol = wave * 32 + n;                          // this lane's key inside the tile
+    const int kcol = (wave & 1) * 32 + n;                    // this lane's key inside its tile
 
     f32x16 dkacc[DBLK], dvacc[DBLK];
 #pragma unroll
@@ -219,74 +294,110 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_kernel(BwdArgs a, int nQB, int
             dvacc[db][i] = 0.f;
         }
 
-    const int c = h * nKB + kb;
-    const int c0 = a.col_ptr[c], c1 = a.col_ptr[c + 1];
-    const size_t stat_base = ((size_t)b * a.H + h) * a.Lq;
-    for (int ci = c0; ci < c1; ++ci) {
-        const int qb = a.row_idx[ci];
-        const int t = a.tile_idx[ci];
-        const int q0 = qb * 64;
-        if (a.causal && (long long)kb * 64 > (long long)q0 + 63 + off) continue;   // hidden from every row of the tile
-        __syncthreads();                                     // the previous tile is consumed
-        issue_tile_loads<D, 2, false>(q_rsrc, Qk, q0, sq_bytes, wave, lane);
-        issue_tile_loads<D, 2, true>(q_rsrc, Qv, q0, sq_bytes, wave, lane);
-        issue_tile_loads<D, 2, false>(g_rsrc, Gk, q0, so_bytes, wave, lane);
-        issue_tile_loads<D, 2, true>(g_rsrc, Gv, q0, so_bytes, wave, lane);
-        if (tid < 64) {                                      // per-query statistics and bitmap rows
-            const int q = q0 + tid;
-            const bool ok = q < a.Lq;
-            s_lse2[tid] = ok ? lse2_of(a.lse[stat_base + q]) : INFINITY;
-            s_delta[tid] = ok ? a.delta[stat_base + q] : 0.f;
-            s_word[tid] = a.bitmaps[(size_t)t * 64 + tid];
+    const int cA = h * nKB + 2 * kp;
+    Merge m;
+    m.ia = a.col_ptr[cA];
+    m.a1 = a.col_ptr[cA + 1];
+    m.ib = m.a1;
+    m.b1 = (2 * kp + 1 < nKB) ? a.col_ptr[cA + 2] : m.a1;
+    const unsigned words_bytes = (unsigned)a.row_ptr[a.H * nQB] * 512u;
+
+    auto issue = [&](const Merge& x, int stage) {
+        lds_u16* base = lds + stage * STAGE;
+        const int q0 = x.key * 64;
+        issue_tile_loads<D, 4, false>(q_rsrc, base, q0, sq_bytes, wave, lane);
+        issue_tile_loads<D, 4, true>(q_rsrc, base + TILE, q0, sq_bytes, wave, lane);
+        issue_tile_loads<D, 4, false>(g_rsrc, base + 2 * TILE, q0, so_bytes, wave, lane);
+        issue_tile_loads<D, 4, true>(g_rsrc, base + 3 * TILE, q0, so_bytes, wave, lane);
+        lds_u16* st = base + 4 * TILE;
+        if (wave == 1 && lane < 16) {                        // 64 floats = 16 lanes x 16 bytes
+            load16_to_lds(lds_addr_of(st), lane * 16, make_rsrc(a.lse + stat_base, stat_bytes), q0 * 4);
         }
+        if (wave == 3 && lane < 16) {
+            load16_to_lds(lds_addr_of(st + 128), lane * 16, make_rsrc(a.delta + stat_base, stat_bytes), q0 * 4);
+        }
+        if (wave == 0 && x.ta >= 0)
+            dma_512(st + 256, a.bitmaps, words_bytes, (long long)a.tile_idx[x.ta] * 512, lane);
+        if (wave == 2 && x.tb >= 0)
+            dma_512(st + 512, a.bitmaps, words_bytes, (long long)a.tile_idx[x.tb] * 512, lane);
+    };
+    // a tile is hidden from every query of its block row when the column starts beyond the row's diagonal
+    auto live = [&](const Merge& x) { return x.key != 0x7fffffff; };
+
+    wait_vmem();
+    settle<KSTEPS>(kreg);
+    settle<KSTEPS>(vreg);
+
+    Merge cur = m;
+    merge_step(cur, a.row_idx);
+    Merge nxt = cur;
+    int stage = 0;
+    if (live(cur)) issue(cur, 0);
+    while (live(cur)) {
+        merge_step(nxt, a.row_idx);
         wait_vmem();
         __syncthreads();
-        f32x16 sacc[2], pacc[2];
-        qk_64<D>(smem, kreg, n, k_swz, sacc);                // S  = Q K^T   (rows: queries, lane: key)
-        qk_64<D>(smem + 2 * TILE, vreg, n, k_swz, pacc);     // dP = dO V^T
-        const bool diag_tile = a.causal && (long long)kb * 64 + 63 > (long long)q0 + off;
+        if (live(nxt)) issue(nxt, stage ^ 1);
+        const int ci = half ? cur.tb : cur.ta;
+        const int q0 = cur.key * 64;
+        const bool hidden = a.causal && (long long)kb * 64 > (long long)q0 + 63 + off;
+        if (have_col && ci >= 0 && !hidden) {
+            uint16_t* base = smem + stage * STAGE;
+            const float* s_lse = reinterpret_cast<const float*>(base + 4 * TILE);
+            const float* s_delta = reinterpret_cast<const float*>(base + 4 * TILE + 128);
+            const uint64_t* s_word = reinterpret_cast<const uint64_t*>(base + 4 * TILE + 256 + half * 256);
+            f32x16 sacc[2], pacc[2];
+            qk_64<D>(base, kreg, n, k_swz, sacc);            // S  = Q K^T   (rows: queries, lane: key)
+            qk_64<D>(base + 2 * TILE, vreg, n, k_swz, pacc); // dP = dO V^T
+            const bool diag_tile = a.causal && (long long)kb * 64 + 63 > (long long)q0 + off;
 #pragma unroll
-        for (int qblk = 0; qblk < 2; ++qblk)
+            for (int qblk = 0; qblk < 2; ++qblk)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int r0 = 32 * qblk + 8 * g + 4 * hh;   // 4 consecutive query rows
-                const float4 l4 = *reinterpret_cast<const float4*>(&s_lse2[r0]);
-                const float4 d4 = *reinterpret_cast<const float4*>(&s_delta[r0]);
-                const float le[4] = {l4.x, l4.y, l4.z, l4.w}, de[4] = {d4.x, d4.y, d4.z, d4.w};
+                for (int g = 0; g < 4; ++g) {
+                    const int r0 = 32 * qblk + 8 * g + 4 * hh;   // 4 consecutive query rows
+                    const float4 l4 = *reinterpret_cast<const float4*>(&s_lse[r0]);
+                    const float4 d4 = *reinterpret_cast<const float4*>(&s_delta[r0]);
+                    const float le[4] = {l4.x, l4.y, l4.z, l4.w}, de[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = 4 * g + e;
-                    bool kept = (s_word[r0 + e] >> kcol) & 1ull;
-                    if (diag_tile) kept = kept && (long long)kb * 64 + kcol <= (long long)q0 + r0 + e + off;
-                    const float p = kept ? __builtin_amdgcn_exp2f(fmaf(sacc[qblk][i], sc, -le[e])) : 0.f;
-                    sacc[qblk][i] = p;                       // P
-                    pacc[qblk][i] = p * (pacc[qblk][i] - de[e]);   // dS
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = 4 * g + e;
+                        bool kept = (s_word[r0 + e] >> kcol) & 1ull;
+                        if (diag_tile) kept = kept && (long long)kb * 64 + kcol <= (long long)q0 + r0 + e + off;
+                        const float p = kept ? __builtin_amdgcn_exp2f(fmaf(sacc[qblk][i], sc, -le[e] * kLog2e)) : 0.f;
+                        sacc[qblk][i] = p;                   // P
+                        pacc[qblk][i] = p * (pacc[qblk][i] - de[e]);   // dS
+                    }
                 }
-            }
-        tr_mm_64<D>(Gv, sacc, dvacc, tr);                    // dV^T += dO^T P
-        tr_mm_64<D>(Qv, pacc, dkacc, tr);                    // dK^T += Q^T dS
+            tr_mm_64<D>(lds + stage * STAGE + 3 * TILE, sacc, dvacc, tr);   // dV^T += dO^T P
+            tr_mm_64<D>(lds + stage * STAGE + TILE, pacc, dkacc, tr);       // dK^T += Q^T dS
+        }
+        cur = nxt;
+        stage ^= 1;
     }
     __syncthreads();                                         // all wavefronts are done with the tiles
-    const int krow0 = kb * 64 + wave * 32;
-    uint16_t* stage = smem + wave * 32 * D;
-    store_rows_bf16<D>(stage, dkacc, a.scale, lane, dKp + (size_t)krow0 * a.sk[2], a.sk[2], a.Lk - krow0);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the staging area is reused
-    store_rows_bf16<D>(stage, dvacc, 1.0f, lane, dVp + (size_t)krow0 * a.sv[2], a.sv[2], a.Lk - krow0);
+    if (have_col) {
+        const int krow0 = kb * 64 + (wave & 1) * 32;
+        uint16_t* stg = smem + wave * 32 * D;
+        store_rows_bf16<D>(stg, dkacc, a.scale, lane, dKp + (size_t)krow0 * a.sk[2], a.sk[2], a.Lk - krow0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the staging area is reused
+        store_rows_bf16<D>(stg, dvacc, 1.0f, lane, dVp + (size_t)krow0 * a.sv[2], a.sv[2], a.Lk - krow0);
+    }
 }
 
 template <int D>
 hipError_t launch_d(const BwdArgs& a, hipStream_t stream)
 {
     const int nQB = (a.Lq + 63) / 64, nKB = (a.Lk + 63) / 64;
+    const int nQP = (nQB + 1) / 2, nKP = (nKB + 1) / 2;
     const long long rows = (long long)a.B * a.H * a.Lq;
     const long long dthreads = rows * (D / 8);
     hipLaunchKernelGGL(bwd_delta_kernel<D>, dim3((unsigned)((dthreads + 255) / 256)), dim3(256), 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((unsigned)(a.B * a.H * nQB)), dim3(128), 0, stream, a, nQB);
+    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((unsigned)(a.B * a.H * nQP)), dim3(256), 0, stream, a, nQB, nQP);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bwd_dkv_kernel<D>, dim3((unsigned)(a.B * a.H * nKB)), dim3(128), 0, stream, a, nQB, nKB);
+    hipLaunchKernelGGL(bwd_dkv_kernel<D>, dim3((unsigned)(a.B * a.H * nKP)), dim3(256), 0, stream, a, nQB, nKB, nKP);
     return hipGetLastError();
 }
 

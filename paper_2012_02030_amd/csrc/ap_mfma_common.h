@@ -46,6 +46,14 @@ __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" 
 typedef __attribute__((ext_vector_type(4))) int rsrc_t;
 __device__ __forceinline__ void load16_to_lds(unsigned lds_addr, int voff, rsrc_t rsrc, int soff)
 {
+    // the descriptor and the scalar offset are wave-uniform by construction; say so where the
+    // compiler cannot see it (values that went through memory or a loop), else it picks VGPRs
+    rsrc.x = __builtin_amdgcn_readfirstlane(rsrc.x);
+    rsrc.y = __builtin_amdgcn_readfirstlane(rsrc.y);
+    rsrc.z = __builtin_amdgcn_readfirstlane(rsrc.z);
+    rsrc.w = __builtin_amdgcn_readfirstlane(rsrc.w);
+    soff = __builtin_amdgcn_readfirstlane(soff);
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
