@@ -166,6 +166,51 @@ def test_mask_construction_arguments(L):
     assert prune(ws_bytes=wp - 1) == ap.AP_ERR_CAPACITY
 
 
+def test_backward_arguments(L):
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+    assert ap.ap_bwd_workspace_bytes(4, 16, 4096) == 4 * 16 * 4096 * 4
+    assert ap.ap_bwd_workspace_bytes(4, 0, 4096) == 0
+    ws = ap.ap_bwd_workspace_bytes(1, 2, 64)
+
+    def bwd(**over):
+        a = dict(Q=fake, K=fake + 0x100000, V=fake + 0x200000, O=fake + 0x300000, dO=fake + 0x400000,
+                 lse=fake + 0x500000, dQ=fake + 0x600000, dK=fake + 0x700000, dV=fake + 0x800000,
+                 dtype=ap.AP_BF16, B=1, H=2, Lq=64, Lk=64, D=64, sq=s, sk=s, sv=s, so=s, row_ptr=fake,
+                 col_idx=fake, bitmaps=fake, col_ptr=fake, row_idx=fake, tile_idx=fake, bm=64, bn=64,
+                 causal=0, scale=0.0, ws=fake, ws_bytes=ws)
+        a.update(over)
+        return L.ap_sparse_attn_bwd(a["Q"], a["K"], a["V"], a["O"], a["dO"], a["lse"], a["dQ"], a["dK"],
+                                    a["dV"], a["dtype"], a["B"], a["H"], a["Lq"], a["Lk"], a["D"], a["sq"],
+                                    a["sk"], a["sv"], a["so"], a["row_ptr"], a["col_idx"], a["bitmaps"],
+                                    a["col_ptr"], a["row_idx"], a["tile_idx"], a["bm"], a["bn"],
+                                    a["causal"], a["scale"], a["ws"], a["ws_bytes"], None)
+
+    assert bwd(dO=None) == ap.AP_ERR_INVALID_ARG
+    assert bwd(lse=None) == ap.AP_ERR_INVALID_ARG
+    assert bwd(col_ptr=None) == ap.AP_ERR_INVALID_ARG
+    assert bwd(ws=None) == ap.AP_ERR_INVALID_ARG
+    assert bwd(B=0) == ap.AP_ERR_INVALID_ARG
+    assert bwd(dQ=fake) == ap.AP_ERR_INVALID_ARG                               # dQ aliases Q
+    assert bwd(dV=fake + 0x700000) == ap.AP_ERR_INVALID_ARG                    # dV aliases dK
+    assert bwd(dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    assert bwd(D=48) == ap.AP_ERR_UNSUPPORTED
+    assert bwd(bm=128) == ap.AP_ERR_UNSUPPORTED
+    assert bwd(causal=1, Lq=128, Lk=64) == ap.AP_ERR_INVALID_ARG
+    assert bwd(dK=fake + 0x700008) == ap.AP_ERR_INVALID_ARG                    # not 16-byte aligned
+    assert bwd(ws_bytes=ws - 1) == ap.AP_ERR_CAPACITY
+    bad = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 60)
+    assert bwd(so=bad) == ap.AP_ERR_INVALID_ARG
+
+    tr = L.ap_build_layout_transpose
+    assert tr(None, fake, 2, 64, 64, 64, 64, 8, fake, fake, fake, None) == ap.AP_ERR_INVALID_ARG
+    assert tr(fake, fake, 2, 64, 64, 64, 64, 8, fake, None, fake, None) == ap.AP_ERR_INVALID_ARG
+    assert tr(fake, fake, 0, 64, 64, 64, 64, 8, fake, fake, fake, None) == ap.AP_ERR_INVALID_ARG
+    assert tr(fake, fake, 2, 64, 64, 48, 64, 8, fake, fake, fake, None) == ap.AP_ERR_UNSUPPORTED
+    assert tr(fake, fake, 2, 64, 64, 64, 64, -1, fake, fake, fake, None) == ap.AP_ERR_INVALID_ARG
+    assert tr(fake, fake + 2, 2, 64, 64, 64, 64, 8, fake, fake, fake, None) == ap.AP_ERR_INVALID_ARG
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ap, "_lib", None)
     monkeypatch.setattr(ap, "LIB_PATH", "/nonexistent/libap_mi355x.so")
