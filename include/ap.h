@@ -173,6 +173,37 @@ ap_status ap_sparse_attn_fwd(const void *Q, const void *K, const void *V, void *
                              void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Masked attention forward for few queries against many keys (the Transformer-XL setting of
+ * Section 4.1: a short segment attends to a long cached memory; the mask of such a layer is
+ * Lq x Lk with Lk >> Lq and the causal limit is aligned bottom-right).
+ *
+ * Same arguments, same result (up to rounding) as ap_sparse_attn_fwd, but the tiles (or
+ * schedule entries) of every block row are cut into `splits` contiguous chunks that run as
+ * separate workgroups; each writes a normalised fp32 partial output and its log-sum-exp to the
+ * workspace and a second kernel merges them:
+ *     lse = ln sum_s exp(lse_s),   O = sum_s exp(lse_s - lse) O_s.
+ * With one or two block rows per (batch, head) the ordinary call would use B*H*ceil(Lq/64)
+ * workgroups; choose splits so that this number times splits reaches a few per compute unit.
+ *
+ *   splits        >= 1 (1 is allowed and only adds the merge), at most 1024
+ *   workspace     device scratch of at least ap_fwd_split_workspace_bytes(B, H, Lq, D, splits)
+ *                 bytes, 16-byte aligned
+ *
+ * Supported: dtype = AP_BF16, block_m = block_n = 64, D in {32, 64, 128}.  Deterministic.
+ * ------------------------------------------------------------------------------------------- */
+size_t ap_fwd_split_workspace_bytes(int B, int H, int Lq, int D, int splits);
+
+ap_status ap_sparse_attn_fwd_split(const void *Q, const void *K, const void *V, void *O, float *lse,
+                                   ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                   const int64_t *stride_q, const int64_t *stride_k,
+                                   const int64_t *stride_v, const int64_t *stride_o,
+                                   const int32_t *row_ptr, const int32_t *col_idx,
+                                   const uint64_t *bitmaps, int block_m, int block_n,
+                                   const ap_schedule *sched, int causal, float softmax_scale,
+                                   int splits, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Backward pass of masked attention (Section 3.2, algorithm step 4: the pruned model F' is
  * trained, which needs the gradients of the masked-attention equation).
  *

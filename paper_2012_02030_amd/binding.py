@@ -26,6 +26,7 @@ AP_BF16 = 1
 
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
            "ap_build_layout", "ap_build_schedule", "ap_sparse_attn_fwd",
+           "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
            "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
            "ap_attention_maps_workspace_bytes", "ap_accumulate_attention_maps",
            "ap_prune_mask_workspace_bytes", "ap_prune_mask")
@@ -74,6 +75,14 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(i64), ctypes.POINTER(i64),
                                          vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
                                          ctypes.c_float, vp]
+        L.ap_fwd_split_workspace_bytes.restype = ctypes.c_size_t
+        L.ap_fwd_split_workspace_bytes.argtypes = [i32] * 5
+        L.ap_sparse_attn_fwd_split.restype = i32
+        L.ap_sparse_attn_fwd_split.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                               ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                               ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                               vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
+                                               ctypes.c_float, i32, vp, ctypes.c_size_t, vp]
         L.ap_build_layout_transpose.restype = i32
         L.ap_build_layout_transpose.argtypes = [vp, vp, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
         L.ap_bwd_workspace_bytes.restype = ctypes.c_size_t
@@ -250,6 +259,46 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
         int(bool(causal)), float(softmax_scale), _stream_ptr(stream))
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_fwd")
+    return out, lse
+
+
+def ap_fwd_split_workspace_bytes(B: int, H: int, Lq: int, D: int, splits: int) -> int:
+    return int(lib().ap_fwd_split_workspace_bytes(B, H, Lq, D, splits))
+
+
+def ap_sparse_attn_fwd_split(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout: Layout,
+                             splits: int, causal: bool = False, softmax_scale: float = 0.0,
+                             out: Optional[torch.Tensor] = None, return_lse: bool = True,
+                             stream: Optional[torch.cuda.Stream] = None,
+                             sched: Optional[Schedule] = None):
+    """ap_sparse_attn_fwd with the entries of every block row cut into `splits` chunks (bf16,
+    block_m 64): for few queries against many keys.  Returns (O, lse).  Asynchronous."""
+    if Q.dtype != torch.bfloat16 or K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise ValueError("Q, K, V must be bfloat16")
+    B, H, Lq, D = Q.shape
+    Lk = K.shape[2]
+    if tuple(K.shape) != (B, H, Lk, D) or tuple(V.shape) != (B, H, Lk, D):
+        raise ValueError("K/V shape mismatch")
+    if (H, Lq, Lk) != (layout.H, layout.Lq, layout.Lk):
+        raise ValueError("layout was built for other sizes")
+    if sched is not None and sched.causal != bool(causal):
+        raise ValueError("schedule was built with causal=%s" % sched.causal)
+    cs = sched.c_struct() if sched is not None else None
+    if out is None:
+        out = torch.empty((B, H, Lq, D), dtype=Q.dtype, device=Q.device)
+    lse = torch.empty((B, H, Lq), dtype=torch.float32, device=Q.device) if return_lse else None
+    ws_bytes = ap_fwd_split_workspace_bytes(B, H, Lq, D, splits)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=Q.device)
+    st = lib().ap_sparse_attn_fwd_split(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+        lse.data_ptr() if lse is not None else None, AP_BF16, B, H, Lq, Lk, D,
+        _strides3(Q), _strides3(K), _strides3(V), _strides3(out),
+        layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
+        layout.block_m, layout.block_n, ctypes.byref(cs) if cs is not None else None,
+        int(bool(causal)), float(softmax_scale), int(splits), ws.data_ptr(), ws_bytes,
+        _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_sparse_attn_fwd_split")
     return out, lse
 
 

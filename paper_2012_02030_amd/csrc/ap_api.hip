@@ -89,13 +89,21 @@ ap_status ap_build_schedule(const int32_t* row_ptr, const int32_t* col_idx, cons
     return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
-ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* lse,
-                             ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
-                             const int64_t* stride_q, const int64_t* stride_k,
-                             const int64_t* stride_v, const int64_t* stride_o,
-                             const int32_t* row_ptr, const int32_t* col_idx,
-                             const uint64_t* bitmaps, int block_m, int block_n,
-                             const ap_schedule* sched, int causal, float softmax_scale, void* stream)
+size_t ap_fwd_split_workspace_bytes(int B, int H, int Lq, int D, int splits)
+{
+    if (B <= 0 || H <= 0 || Lq <= 0 || D <= 0 || splits <= 0) return 0;
+    return (size_t)splits * (size_t)B * (size_t)H * (size_t)Lq * ((size_t)D + 1) * sizeof(float);
+}
+
+// splits = 0: the ordinary forward call; splits >= 1: the split variant with its workspace
+static ap_status fwd_common(const void* Q, const void* K, const void* V, void* O, float* lse,
+                            ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                            const int64_t* stride_q, const int64_t* stride_k,
+                            const int64_t* stride_v, const int64_t* stride_o,
+                            const int32_t* row_ptr, const int32_t* col_idx,
+                            const uint64_t* bitmaps, int block_m, int block_n,
+                            const ap_schedule* sched, int causal, float softmax_scale, int splits,
+                            void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!Q || !K || !V || !O || !stride_q || !stride_k || !stride_v || !stride_o || !row_ptr ||
         !col_idx || !bitmaps)
@@ -133,6 +141,13 @@ ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* 
                              (long long)Lk * stride_v[2] * 2 >= 2147483647LL))
         return AP_ERR_UNSUPPORTED;
 
+    if (splits > 0) {
+        if (!workspace || !aligned(workspace, 16)) return AP_ERR_INVALID_ARG;
+        if (dtype != AP_BF16 || block_m != 64) return AP_ERR_UNSUPPORTED;
+        if (splits > 1024 || nQB * H * B * splits >= 2147483647LL) return AP_ERR_UNSUPPORTED;
+        if (workspace_bytes < ap_fwd_split_workspace_bytes(B, H, Lq, D, splits)) return AP_ERR_CAPACITY;
+    }
+
     ap::FwdArgs a;
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
     a.B = B; a.H = H; a.Lq = Lq; a.Lk = Lk; a.D = D;
@@ -147,13 +162,46 @@ ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* 
         a.sched = ap::Schedule{sched->cnt, sched->start, sched->cols, sched->bitmaps};
     else
         a.sched = ap::Schedule{nullptr, nullptr, nullptr, nullptr};
+    a.splits = splits > 0 ? splits : 1;
+    a.part_o = (float*)workspace;
+    a.part_lse = a.part_o ? a.part_o + (size_t)a.splits * B * H * Lq * D : nullptr;
 
     hipError_t e;
-    if (dtype == AP_BF16)
+    if (splits > 0)
+        e = ap::launch_fwd_split(a, (hipStream_t)stream);
+    else if (dtype == AP_BF16)
         e = ap::launch_fwd_mfma(a, (hipStream_t)stream);
     else
         e = ap::launch_fwd_valu(a, false, (hipStream_t)stream);
     return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* lse,
+                             ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                             const int64_t* stride_q, const int64_t* stride_k,
+                             const int64_t* stride_v, const int64_t* stride_o,
+                             const int32_t* row_ptr, const int32_t* col_idx,
+                             const uint64_t* bitmaps, int block_m, int block_n,
+                             const ap_schedule* sched, int causal, float softmax_scale, void* stream)
+{
+    return fwd_common(Q, K, V, O, lse, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v, stride_o,
+                      row_ptr, col_idx, bitmaps, block_m, block_n, sched, causal, softmax_scale, 0,
+                      nullptr, 0, stream);
+}
+
+ap_status ap_sparse_attn_fwd_split(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                   ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                   const int64_t* stride_q, const int64_t* stride_k,
+                                   const int64_t* stride_v, const int64_t* stride_o,
+                                   const int32_t* row_ptr, const int32_t* col_idx,
+                                   const uint64_t* bitmaps, int block_m, int block_n,
+                                   const ap_schedule* sched, int causal, float softmax_scale,
+                                   int splits, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (splits <= 0) return AP_ERR_INVALID_ARG;
+    return fwd_common(Q, K, V, O, lse, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v, stride_o,
+                      row_ptr, col_idx, bitmaps, block_m, block_n, sched, causal, softmax_scale, splits,
+                      workspace, workspace_bytes, stream);
 }
 
 ap_status ap_build_layout_transpose(const int32_t* row_ptr, const int32_t* col_idx, int H, int Lq,

@@ -45,7 +45,10 @@ using namespace mfma;
 // SCHED = false: walk the stored tiles of the layout (64 consecutive keys each, causal limit
 // applied here).  SCHED = true: walk the entries of a visit schedule (consecutive or gathered
 // keys, causal limit already folded into the bitmaps).
-template <int D, int NW, int STAGES, bool SCHED>
+// SPLIT = true: the entries of a block row are cut into a.splits contiguous chunks, one workgroup
+// each, which write a normalised fp32 partial output and its log-sum-exp for merge_splits_kernel
+// (few queries against many keys: one workgroup per block row would leave the chip idle).
+template <int D, int NW, int STAGES, bool SCHED, bool SPLIT = false>
 __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB, int xcd_chunk)
 {
     constexpr int BM = 32 * NW;
@@ -76,6 +79,11 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
     // (batch, head) pairs so that the block rows sharing K and V also share an L2.
     int bid = blockIdx.x;
     if (xcd_chunk > 0) bid = (bid & 7) * xcd_chunk + (bid >> 3);
+    int split = 0;
+    if (SPLIT) {
+        split = bid % a.splits;
+        bid /= a.splits;
+    }
     const int qb = nQB - 1 - (bid % nQB);                    // long causal rows first
     const int h = (bid / nQB) % a.H;
     const int b = bid / (nQB * a.H);
@@ -112,8 +120,14 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
     const float sc = a.scale * kLog2e;
 
     const int r = h * nQB + qb;
-    const int t_begin = a.row_ptr[r];
+    int t_begin = a.row_ptr[r];
     int nt = SCHED ? a.sched.cnt[r] : a.row_ptr[r + 1] - t_begin;
+    if (SPLIT) {                                             // this workgroup's chunk of the entries
+        const int chunk = (nt + a.splits - 1) / a.splits;
+        const int e0 = min(nt, split * chunk);
+        t_begin += e0;
+        nt = min(nt - e0, chunk);
+    }
     const long long off = (long long)a.Lk - a.Lq;
     const long long diag = (long long)qrow + off;            // last visible key if causal
     const uint64_t* words = SCHED ? a.sched.bitmaps : a.bitmaps;
@@ -456,6 +470,22 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
         ltot = __uint_as_float(r[0]) + __uint_as_float(r[1]);
     }
     const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+    if (SPLIT) {                                             // partial result: fp32, normalised by its own sum
+        const size_t prow = (((size_t)split * a.B + b) * a.H + h) * a.Lq + qrow;
+        if (row_ok) {
+            float* po = a.part_o + prow * D;
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4)
+                    *reinterpret_cast<float4*>(po + 32 * db + 8 * g4 + 4 * hh) =
+                        make_float4(oacc[db][4 * g4] * inv, oacc[db][4 * g4 + 1] * inv,
+                                    oacc[db][4 * g4 + 2] * inv, oacc[db][4 * g4 + 3] * inv);
+            if (hh == 0)
+                a.part_lse[prow] = ltot > 0.f ? (m * sc + __builtin_amdgcn_logf(ltot)) * kLn2 : -INFINITY;
+        }
+        return;
+    }
     __syncthreads();                                         // all wavefronts are done with K/V in LDS
     uint16_t* ostage = smem + wave * 32 * D;                 // this wavefront's 32 rows
     {
@@ -504,7 +534,75 @@ hipError_t launch_one(const FwdArgs& a, hipStream_t stream)
     return hipGetLastError();
 }
 
+// O = sum_s exp(lse_s - lse) O_s with lse = ln sum_s exp(lse_s): one thread per (row, 4 elements).
+template <int D>
+__global__ __launch_bounds__(256) void merge_splits_kernel(FwdArgs a)
+{
+    constexpr int TPR = D / 4;                               // threads per row
+    const long long rows = (long long)a.B * a.H * a.Lq;
+    const long long row = ((long long)blockIdx.x * 256 + threadIdx.x) / TPR;
+    const int part = threadIdx.x % TPR;
+    if (row >= rows) return;
+    float mx = -INFINITY;
+    for (int s = 0; s < a.splits; ++s) mx = fmaxf(mx, a.part_lse[(size_t)s * rows + row]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float tot = 0.f;
+    if (mx != -INFINITY) {
+        for (int s = 0; s < a.splits; ++s) {
+            const float w = __expf(a.part_lse[(size_t)s * rows + row] - mx);   // 0 for an empty chunk
+            if (w == 0.f) continue;                          // its partial output may be anything finite
+            const float4 o = *reinterpret_cast<const float4*>(a.part_o + ((size_t)s * rows + row) * D + part * 4);
+            acc.x = fmaf(w, o.x, acc.x);
+            acc.y = fmaf(w, o.y, acc.y);
+            acc.z = fmaf(w, o.z, acc.z);
+            acc.w = fmaf(w, o.w, acc.w);
+            tot += w;
+        }
+        const float inv = 1.f / tot;
+        acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+    }
+    const int i = (int)(row % a.Lq);
+    const long long bh = row / a.Lq;
+    const int h = (int)(bh % a.H);
+    const long long b = bh / a.H;
+    uint16_t* dst = (uint16_t*)a.O + (size_t)b * a.so[0] + (size_t)h * a.so[1] + (size_t)i * a.so[2] + part * 4;
+    uint2 w2;
+    w2.x = pack_bf16_rne(acc.x, acc.y);
+    w2.y = pack_bf16_rne(acc.z, acc.w);
+    *reinterpret_cast<uint2*>(dst) = w2;
+    if (a.lse && part == 0) a.lse[row] = mx == -INFINITY ? -INFINITY : mx + __logf(tot);
+}
+
+template <int D>
+hipError_t launch_split_d(const FwdArgs& a, hipStream_t stream)
+{
+    const int nQB = (a.Lq + 63) / 64;
+    const long long blocks = (long long)nQB * a.H * a.B * a.splits;
+    constexpr int ST = D == 128 ? 1 : 2;
+    if (a.sched.cnt)
+        hipLaunchKernelGGL((fwd_mfma_kernel<D, 2, ST, true, true>), dim3((unsigned)blocks), dim3(128), 0,
+                           stream, a, nQB, 0);
+    else
+        hipLaunchKernelGGL((fwd_mfma_kernel<D, 2, ST, false, true>), dim3((unsigned)blocks), dim3(128), 0,
+                           stream, a, nQB, 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const long long threads = (long long)a.B * a.H * a.Lq * (D / 4);
+    hipLaunchKernelGGL(merge_splits_kernel<D>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_fwd_split(const FwdArgs& a, hipStream_t stream)
+{
+    switch (a.D) {
+    case 32: return launch_split_d<32>(a, stream);
+    case 64: return launch_split_d<64>(a, stream);
+    case 128: return launch_split_d<128>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
 
 hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream)
 {

@@ -43,12 +43,17 @@ struct FwdArgs {
     int causal;
     float scale;                    // already resolved (> 0)
     Schedule sched;                 // all null: walk the layout itself
+    int splits;                     // split path only: chunks per block row
+    float* part_o;                  // [splits, B, H, Lq, D] fp32 partial outputs
+    float* part_lse;                // [splits, B, H, Lq]
 };
 
 // fp32-arithmetic kernel (one query per lane); handles fp32 and bf16 storage, block 64x64
 hipError_t launch_fwd_valu(const FwdArgs& a, bool bf16, hipStream_t stream);
 // bf16 matrix-core kernel; block_m 64 or 128, block_n 64
 hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream);
+// same result, the entries of every block row cut into a.splits chunks and merged (block_m 64)
+hipError_t launch_fwd_split(const FwdArgs& a, hipStream_t stream);
 
 // ---- backward pass (ap_layout_transpose.hip, ap_attn_bwd.hip)
 hipError_t launch_layout_transpose(const int32_t* row_ptr, const int32_t* col_idx, int H, int nQB,
