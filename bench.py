@@ -39,6 +39,8 @@ def parse():
     p.add_argument("--no-sched", action="store_true", help="walk the layout itself instead of the visit schedule")
     p.add_argument("--only", action="store_true", help="skip the per-config table and the CPU baseline")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    p.add_argument("--only-split", action="store_true",
+                   help="time only the split forward call on the long-memory shape X1 and print its figures")
     p.add_argument("--only-backward", action="store_true",
                    help="time only the backward pass at the workload's shape and print its figures")
     p.add_argument("--no-backward", action="store_true", help="skip the timing of the backward pass")
@@ -352,6 +354,57 @@ def main():
             "layout_transpose_ms": tr_ms,
         }
 
+    def run_split_forward(cfg, steps):
+        """Few queries against a long memory: the ordinary call (one workgroup per block row)
+        against the split call, same layout and schedule."""
+        mask_np = synth.make_mask(cfg)
+        lay = ap.ap_build_layout(torch.from_numpy(mask_np).to(dev), 64, 64)
+        sched = ap.ap_build_schedule(lay, causal=cfg.causal, min_cols=args.min_cols)
+        q, k, v = (torch.from_numpy(x).to(torch.bfloat16).to(dev) for x in synth.make_qkv(cfg))
+        out = torch.empty_like(q)
+
+        def timed(fn, n):
+            fn()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            torch.cuda.synchronize()
+            evs[0].record()
+            for i in range(n):
+                fn()
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            return float(np.mean([evs[i].elapsed_time(evs[i + 1]) for i in range(n)]))
+
+        plain_ms = timed(lambda: ap.ap_sparse_attn_fwd(q, k, v, lay, causal=cfg.causal, out=out, sched=sched), steps)
+        best = None
+        table = {}
+        for splits in (4, 8, 16, 32):
+            ms = timed(lambda: ap.ap_sparse_attn_fwd_split(q, k, v, lay, splits, causal=cfg.causal, out=out,
+                                                          sched=sched), steps)
+            table[str(splits)] = ms
+            if best is None or ms < table[str(best)]:
+                best = splits
+        kept = int(mask_np.sum())
+        cols = int((mask_np.any(axis=1)).sum())                   # distinct (head, key) pairs with a kept entry
+        alg = 2 * cfg.B * (2 * cols * cfg.D + 2 * cfg.H * cfg.Lq * cfg.D)   # their K and V rows, Q and O
+        ms = table[str(best)]
+        return {
+            "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D, "causal": cfg.causal},
+            "entries_visited": int(sched.cnt.sum().item()),
+            "tiles_stored": int(lay.nnz.item()),
+            "plain_call_ms": plain_ms,
+            "split_call_ms": table,
+            "best_splits": best,
+            "speedup_vs_plain_call": plain_ms / ms,
+            "kept_tflops": 4.0 * cfg.D * kept * cfg.B / (ms * 1e-3) / 1e12,
+            "hbm_alg_bytes": alg,
+            "hbm_gbs": alg / (ms * 1e-3) / 1e9,
+            "hbm_roofline_frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        }
+
+    if args.only_split:
+        print(json.dumps({"split_forward": run_split_forward(synth.EXTRA_CONFIGS["X1"], args.steps)}), flush=True)
+        return
+
     if args.only_backward:
         cfg = synth.CONFIGS[args.workload]
         print(json.dumps({"backward": run_backward(cfg, synth.make_mask(cfg), args.steps)}), flush=True)
@@ -415,6 +468,12 @@ def main():
         mask_construction = run_mask_construction(head, 10)
         torch.cuda.empty_cache()
 
+    split_forward = None
+    if not args.only:
+        log("timing the split forward call on the long-memory shape X1 ...")
+        split_forward = run_split_forward(synth.EXTRA_CONFIGS["X1"], 20)
+        torch.cuda.empty_cache()
+
     backward = None
     if not args.only and not args.no_backward:
         log("timing the backward pass at the", head.name, "shape ...")
@@ -454,6 +513,7 @@ def main():
         "parity": parity,
         "mask_construction": mask_construction,
         "backward": backward,
+        "split_forward": split_forward,
         "per_config": per_config,
     }
     print(json.dumps(out), flush=True)

@@ -52,6 +52,13 @@ CONFIGS = {
 }
 
 
+# A further shape, not one of the five benchmark configurations: a 64-token segment attending to a
+# long memory plus itself (the Transformer-XL setting of Section 4.1), for the split forward call.
+EXTRA_CONFIGS = {
+    "X1": Config("X1", 6, 4, 16, 64, 16384, 128, "bf16", True, 0.10, band=128, spike=0.001),
+}
+
+
 def _keep_top(score: np.ndarray, valid: np.ndarray | None, frac: float) -> np.ndarray:
     """Boolean map that keeps exactly round(frac * #valid) largest valid entries."""
     flat = score.astype(score.dtype, copy=True).ravel()
@@ -87,11 +94,11 @@ def head_mask(cfg: Config, h: int) -> np.ndarray:
         score = 4.0 * (np.abs(i - j) <= cfg.band // 2) + 4.0 * ((j == 0) | (j == Lk - 1)) + noise
         keep = _keep_top(score, None, cfg.keep)
         keep |= (i == j)
-    elif cfg.name in ("C3", "C5"):
+    elif cfg.name in ("C3", "C5", "X1"):
         w = np.float32(cfg.band)
         gauss = rng.standard_normal((Lq, Lk), dtype=np.float32)
         spikes = rng.random((Lq, Lk), dtype=np.float32) < np.float32(cfg.spike)
-        d = (i - j).astype(np.float32)
+        d = (i + (Lk - Lq) - j).astype(np.float32)           # distance behind the query's own position
         inband = ((d >= 0) & (d < w)).astype(np.float32)
         base = inband * (np.float32(1.0) - d / w)
         with np.errstate(divide="ignore", invalid="ignore"):
@@ -100,7 +107,7 @@ def head_mask(cfg: Config, h: int) -> np.ndarray:
         score = base * np.exp(np.float32(0.1) * gauss) + np.float32(5.0) * spikes.astype(np.float32)
         del gauss, spikes, base, inband, d
         keep = _keep_top(score, causal_valid, cfg.keep)
-        keep |= (i == j)
+        keep |= (j == i + (Lk - Lq))
     elif cfg.name == "C4":
         jitter = rng.integers(-8, 9, Lq)
         noise = rng.lognormal(0.0, 1.0, (Lq, Lk))
