@@ -166,6 +166,33 @@ def test_mask_construction_arguments(L):
     assert prune(ws_bytes=wp - 1) == ap.AP_ERR_CAPACITY
 
 
+def test_split_forward_arguments(L):
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+    assert ap.ap_fwd_split_workspace_bytes(4, 16, 64, 128, 8) == 8 * 4 * 16 * 64 * 129 * 4
+    assert ap.ap_fwd_split_workspace_bytes(4, 16, 64, 128, 0) == 0
+    ws = ap.ap_fwd_split_workspace_bytes(1, 2, 64, 64, 4)
+
+    def call(**over):
+        a = dict(Q=fake, K=fake + 0x100000, V=fake + 0x200000, O=fake + 0x300000, dtype=ap.AP_BF16, bm=64,
+                 splits=4, ws=fake, ws_bytes=ws, sq=s)
+        a.update(over)
+        return L.ap_sparse_attn_fwd_split(a["Q"], a["K"], a["V"], a["O"], None, a["dtype"], 1, 2, 64, 64, 64,
+                                          a["sq"], s, s, s, fake, fake, fake, a["bm"], 64, None, 0, 0.0,
+                                          a["splits"], a["ws"], a["ws_bytes"], None)
+
+    assert call(splits=0) == ap.AP_ERR_INVALID_ARG
+    assert call(Q=None) == ap.AP_ERR_INVALID_ARG
+    assert call(ws=None) == ap.AP_ERR_INVALID_ARG
+    assert call(ws=0x1008) == ap.AP_ERR_INVALID_ARG
+    assert call(dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    assert call(bm=128) == ap.AP_ERR_UNSUPPORTED
+    assert call(splits=2000) == ap.AP_ERR_UNSUPPORTED
+    assert call(ws_bytes=ws - 1) == ap.AP_ERR_CAPACITY
+    bad = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 60)
+    assert call(sq=bad) == ap.AP_ERR_INVALID_ARG
+
+
 def test_backward_arguments(L):
     fake = 0x1000
     s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
