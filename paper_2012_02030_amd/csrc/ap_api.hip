@@ -335,7 +335,8 @@ ap_status ap_prune_mask(const float* abar, int H, int Lq, int Lk, int causal, do
     if (H <= 0 || Lq <= 0 || Lk <= 0) return AP_ERR_INVALID_ARG;
     if (!(prune_fraction >= 0.0 && prune_fraction <= 1.0)) return AP_ERR_INVALID_ARG;   // also NaN
     if (causal && Lk < Lq) return AP_ERR_INVALID_ARG;
-    if ((long long)H * Lq >= 2147483647LL) return AP_ERR_UNSUPPORTED;
+    // positions inside a pair of rows are 32-bit
+    if ((long long)H * Lq >= 2147483647LL || Lk > (1 << 30)) return AP_ERR_UNSUPPORTED;
     if (!aligned(abar, 16) || !aligned(mask, 4) || !aligned(tau_out, 4) || !aligned(workspace, 16))
         return AP_ERR_INVALID_ARG;
     if (workspace_bytes < ap::prune_mask_workspace_bytes()) return AP_ERR_CAPACITY;

@@ -95,7 +95,8 @@ __global__ void select_init_kernel(Workspace w, unsigned long long rank, unsigne
 // pair of rows i and Lq-1-i of a head, whose visible prefixes together hold Lk + (Lk - Lq) + 1
 // entries whatever i is.  Inside a unit the two prefixes are laid end to end (the first padded
 // to a multiple of 4 positions, so that no quad of positions spans both rows and 128-bit loads
-// stay aligned) and lane l takes the 4 entries at position 256 * step + 4 * l.  All row arithmetic is wave-uniform.
+// stay aligned) and lane l takes the 4 entries at position 256 * step + 4 * l.  All row
+// arithmetic is wave-uniform.
 struct Walk {
     const float* abar;
     long long units;
@@ -174,7 +175,6 @@ __device__ __forceinline__ void load_quads(const Walk& w, const Unit& u, int pos
         q[k].v = make_float4(e[0], e[1], e[2], e[3]);
     }
 }
-
 
 template <int LEVEL> struct Digit;
 template <> struct Digit<0> { static constexpr int shift = 17, bits = 15; };
