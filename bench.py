@@ -155,6 +155,69 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / (reps * n)
 
+    def measured_peaks():
+        """What this GPU reaches on a plain device copy and on a library bf16 GEMM, as a second
+        yardstick next to the published peaks."""
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(2):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 2.0 * n * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
+        m = 8192
+        a_ = torch.randn((m, m), device=dev, dtype=torch.float32).to(torch.bfloat16)
+        b_ = torch.randn((m, m), device=dev, dtype=torch.float32).to(torch.bfloat16)
+        for _ in range(2):
+            torch.matmul(a_, b_)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            torch.matmul(a_, b_)
+        e1.record()
+        torch.cuda.synchronize()
+        gemm_tflops = 2.0 * m * m * m * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        del a_, b_
+        torch.cuda.empty_cache()
+        return {"hbm_copy_gbs": copy_gbs, "hbm_copy": "1 GiB device-to-device copy, read + write bytes",
+                "bf16_gemm_tflops": gemm_tflops, "bf16_gemm": "torch.matmul 8192^3 bf16 (library GEMM)"}
+
+    def oracle_check(cfg, mask_np, set0, out, lse, threads_note=True):
+        """The fp64 oracle on the whole configuration: wall time on all host threads (and on one,
+        for the small configurations), and the largest deviation of the GPU result from it."""
+        import ctypes
+
+        import oracle
+        q, k, v = set0
+        rq, rk, rv = (x.to(torch.float64).cpu().numpy() for x in (q, k, v))
+        t0 = time.perf_counter()
+        O_ref, lse_ref = oracle.masked_attention(rq, rk, rv, mask_np, causal=cfg.causal)
+        all_s = time.perf_counter() - t0
+        res = {"oracle_ms_all_threads": all_s * 1e3, "oracle_threads": oracle.num_threads()}
+        if cfg.name != "C5":
+            try:
+                gomp = ctypes.CDLL("libgomp.so.1")
+                nthreads = oracle.num_threads()
+                gomp.omp_set_num_threads(1)
+                t0 = time.perf_counter()
+                oracle.masked_attention(rq, rk, rv, mask_np, causal=cfg.causal)
+                res["oracle_ms_1_thread"] = (time.perf_counter() - t0) * 1e3
+                gomp.omp_set_num_threads(nthreads)
+            except OSError:
+                pass
+        finite = np.isfinite(lse_ref)
+        res["max_abs_err_O"] = float(np.abs(out.to(torch.float64).cpu().numpy() - O_ref).max())
+        res["max_abs_err_lse"] = float(np.abs(lse.to(torch.float64).cpu().numpy()[finite] - lse_ref[finite]).max())
+        res["tolerance"] = 2e-2 if cfg.dtype == "bf16" else 1e-5
+        return res, all_s
+
     def run_config(cfg, mask_np, steps, warmup, block_m, use_graph):
         """AP-mask run and dense-mask run of the same kernel; returns a result dict."""
         dmask = torch.from_numpy(mask_np).to(dev)
@@ -186,6 +249,9 @@ def main():
         dwall_ms, dper = time_calls(cfg, dense_layout, sets, outs, lses, dsteps, max(2, warmup // 4))
         ms = float(np.mean(per))
         dms = float(np.mean(dper))
+        # warm: one buffer set only, so K, V and Q may stay in the 256 MB cache between calls
+        _, wper = time_calls(cfg, layout, sets[:1], outs[:1], lses[:1], max(10, steps // 4), 2, sched)
+        warm_ms = float(np.mean(wper))
         gms = gdms = None
         if use_graph:
             try:
@@ -217,6 +283,7 @@ def main():
             "tiles_max": int(ap.ap_layout_max_tiles(cfg.H, cfg.Lq, cfg.Lk, block_m, 64)),
             "ms_per_call": kernel_ms,
             "ms_per_call_stream_launches": ms,
+            "warm_ms_per_call_stream_launches": warm_ms,
             "ms_per_call_median": float(np.median(per)),
             "ms_per_call_min": float(np.min(per)),
             "wall_ms_per_step": wall_ms,
@@ -456,11 +523,24 @@ def main():
                 continue
             log("timing", name, "...")
             steps = min(args.steps, 200)
-            res, keep = run_config(cfg, synth.make_mask(cfg), steps, args.warmup, args.block_m,
+            cmask = synth.make_mask(cfg)
+            res, keep = run_config(cfg, cmask, steps, args.warmup, args.block_m,
                                    use_graph=(name != "C5"))
+            if not args.no_cpu:
+                kset0, kouts, klses, klayout, ksched = keep
+                q, k, v = kset0
+                ap.ap_sparse_attn_fwd(q, k, v, klayout, causal=cfg.causal, out=kouts[0], lse=klses[0], sched=ksched)
+                torch.cuda.synchronize()
+                res["oracle"], _ = oracle_check(cfg, cmask, kset0, kouts[0], klses[0])
+                del kset0, kouts, klses, klayout, ksched
             del keep
             torch.cuda.empty_cache()
             per_config[name] = res
+
+    peaks = None
+    if not args.only:
+        log("measuring a device copy and a library bf16 GEMM ...")
+        peaks = measured_peaks()
 
     mask_construction = None
     if not args.only and not args.no_mask_construction:
@@ -509,6 +589,10 @@ def main():
                      "algorithmic_bytes_per_launch": head_res["hbm_alg_bytes"]},
         "roofline_dense_run": {"bound": "mfma", "achieved": head_res["dense_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
                                "unit": "TFLOP/s", "frac": head_res["dense_mfma_frac"]},
+        "measured_peaks": peaks,
+        "roofline_vs_measured": None if peaks is None else {
+            "hbm_frac_of_copy_rate": head_res["hbm_gbs"] / peaks["hbm_copy_gbs"],
+            "dense_run_frac_of_gemm_rate": head_res["dense_tflops"] / peaks["bf16_gemm_tflops"]},
         "cpu_baseline": cpu,
         "parity": parity,
         "mask_construction": mask_construction,
