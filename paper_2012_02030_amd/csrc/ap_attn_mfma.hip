@@ -243,11 +243,14 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
         };
         read_group(0);
         if (NG > 1) read_group(1);
+        // matrix instructions of this wavefront go ahead of the vector work of the others on the SIMD
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi) {
             if (gi + 2 < NG) read_group(gi + 2);
             mfma_group(gi);
         }
+        __builtin_amdgcn_s_setprio(0);
         // pin that order: reads of two groups, then (reads of the next group, matrix ops of this one)
         __builtin_amdgcn_sched_group_barrier(0x100, (NG > 1 ? 2 : 1) * 2 * GS, 0);
 #pragma unroll
@@ -327,6 +330,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
         };
         bf16x8 vcur[DBLK], vnext[DBLK];
         read_v(0, vcur);
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             bf16x8 pb;
@@ -339,6 +343,7 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
 #pragma unroll
             for (int db = 0; db < DBLK; ++db) vcur[db] = vnext[db];
         }
+        __builtin_amdgcn_s_setprio(0);
     };
 
     auto apply_causal = [&](uint64_t word, int k0) -> uint64_t {
