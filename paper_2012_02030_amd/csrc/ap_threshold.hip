@@ -287,15 +287,18 @@ __global__ __launch_bounds__(kThreads) void radix_select_kernel(Workspace ws)
 }
 
 // Second sweep: the mask of every entry that the fixed key bits already decide, and the list of
-// the entries they do not decide.  Candidates are staged per wavefront in LDS and moved to the
-// global list kStage at a time, so the global counter sees one atomic per few hundred candidates.
-constexpr int kStage = 256;
+// the entries they do not decide.  Candidates are staged per wavefront in LDS (a lane reserves
+// room for its own with one LDS atomic) and moved to the global list in blocks, so the global
+// counter sees one atomic per few hundred candidates.
+constexpr int kStage = 384;                  // staged candidates per wavefront
+constexpr int kStageFlush = kStage - 256;    // a quad step adds at most 64 lanes x 4 entries
 
 __global__ __launch_bounds__(kThreads) void mask_collect_kernel(Walk w, Workspace ws, uint8_t* mask, int none)
 {
     constexpr int U = 4;
     __shared__ uint32_t s_key[kThreads / 64][kStage];
     __shared__ unsigned long long s_idx[kThreads / 64][kStage];
+    __shared__ uint32_t s_fill[kThreads / 64];
     const uint32_t fixed = ws.st->fixed_bits;
     const uint32_t prefix = ws.st->prefix;
     const bool exact = fixed == 32;                          // tau = prefix, nothing to collect
@@ -305,13 +308,16 @@ __global__ __launch_bounds__(kThreads) void mask_collect_kernel(Walk w, Workspac
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long long nwaves = (long long)gridDim.x * (kThreads / 64);
     const bool vec_ok = (w.Lk & 3) == 0;
-    int fill = 0;                                            // staged candidates of this wavefront
+    if (lane == 0) s_fill[wave] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
 
-    auto flush = [&]() {
+    auto flush = [&]() {                                     // wave-uniform
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");   // staged entries written by other lanes
+        const int fill = (int)__builtin_amdgcn_readfirstlane(s_fill[wave]);
+        if (fill == 0) return;
         uint32_t base = 0;
         if (lane == 0) base = atomicAdd(&ws.st->ncand, (uint32_t)fill);
         base = __shfl(base, 0, 64);
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");   // staged entries written by other lanes
         for (int i = lane; i < fill; i += 64) {
             const uint32_t slot = base + i;
             if (slot < kCap) {                               // always: the bin was chosen to fit
@@ -320,7 +326,8 @@ __global__ __launch_bounds__(kThreads) void mask_collect_kernel(Walk w, Workspac
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        fill = 0;
+        if (lane == 0) s_fill[wave] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     };
 
     for (long long unit = (long long)wave * gridDim.x + blockIdx.x; unit < w.units; unit += nwaves) {
@@ -333,33 +340,27 @@ __global__ __launch_bounds__(kThreads) void mask_collect_kernel(Walk w, Workspac
                 const float ve[4] = {q[k].v.x, q[k].v.y, q[k].v.z, q[k].v.w};
                 uint32_t out = 0;
                 uint32_t keys[4];
-                bool cands[4];
-                bool any = false;
+                uint32_t cmask = 0;                          // which of the 4 entries are candidates
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const bool vis = e < q[k].cnt;
                     keys[e] = key_of(ve[e]);
                     const uint32_t hi = keys[e] >> shift;
-                    const bool keep = vis && (exact ? keys[e] >= prefix : hi > phi);
-                    cands[e] = vis && !exact && hi == phi;
-                    any = any || cands[e];
-                    if (keep) out |= 1u << (8 * e);
+                    if (vis && (exact ? keys[e] >= prefix : hi > phi)) out |= 1u << (8 * e);
+                    if (vis && !exact && hi == phi) cmask |= 1u << e;
                 }
                 const long long lin = u.base[q[k].which] + q[k].col;
-                if (__ballot(any) != 0) {                    // rare enough to keep out of the common path
+                if (__ballot(cmask != 0) != 0) {             // rare enough to keep out of the common path
+                    if (__builtin_amdgcn_readfirstlane(s_fill[wave]) > kStageFlush) flush();
+                    if (cmask != 0) {
+                        uint32_t pos = atomicAdd(&s_fill[wave], (uint32_t)__popc(cmask));
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const unsigned long long ballot = __ballot(cands[e]);
-                        if (ballot) {
-                            const int c = __popcll(ballot);
-                            if (fill + c > kStage) flush();
-                            if (cands[e]) {
-                                const int pos = fill + __popcll(ballot & ((1ull << lane) - 1ull));
+                        for (int e = 0; e < 4; ++e)
+                            if (cmask & (1u << e)) {
                                 s_key[wave][pos] = keys[e];
                                 s_idx[wave][pos] = (unsigned long long)(lin + e);
+                                ++pos;
                             }
-                            fill += c;
-                        }
                     }
                 }
                 // candidates get 0 here, their byte comes later; a quad cut by the visible prefix
@@ -389,9 +390,8 @@ __global__ __launch_bounds__(kThreads) void mask_collect_kernel(Walk w, Workspac
             }
         }
     }
-    if (fill > 0) flush();
+    flush();
 }
-
 
 // One workgroup: tau among the candidates, by radix selection over their undecided low bits.
 __global__ __launch_bounds__(kThreads) void candidate_select_kernel(Workspace ws, float* tau_out)
