@@ -409,9 +409,10 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
         }
     } else {
         // ---- Pipeline B: one K buffer and one V buffer (half the LDS, twice the workgroups per
-        // CU).  K of the next tile and V of the current tile are loaded while the current
-        // tile's softmax runs: K is free once every wavefront has its scores, V once every
-        // wavefront is past the previous tile's second product.  Two barriers per tile.
+        // CU).  V of the current tile is requested as soon as every wavefront is past the previous
+        // tile's second product and travels under Q K^T and the softmax; K of the next tile is
+        // requested as soon as every wavefront has its scores and travels under the softmax and
+        // the second product.  Three barriers per tile.
         lds_u16* Ks = lds;
         lds_u16* Vs = lds + TILE;
         int gcur[NLOAD];                                     // gather keys of the current tile (for its V)
@@ -433,38 +434,41 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
                 s_nxt = tile_start(1);
                 if (SCHED && s_nxt < 0) dma_cols(1, 1);
             }
-            wait_vmem();
-            __syncthreads();
         }
         settle_q();
         for (int it = 0; it < nt; ++it) {
             const int slot = it & 1;
+            wait_vmem();                                     // K and metadata of this tile (keys of the next)
+            __syncthreads();                                 // ... for everybody; the V buffer is free
+            // metadata of later tiles first, so that only the K loads are younger than the V loads
+            int s_nn = 0;
+            if (it + 1 < nt) dma_words(it + 1, slot ^ 1);
+            if (it + 2 < nt) {
+                s_nn = tile_start(it + 2);
+                if (SCHED && s_nn < 0) dma_cols(it + 2, slot);
+            }
+            if (!SCHED || s_cur >= 0) issue_tile_loads<D, NW, true>(v_rsrc, Vs, s_cur, sv_bytes, wave, lane);
+            else issue_gather_loads<D, NW, true>(v_rsrc, Vs, gcur, sv_bytes, wave, lane);
             const uint64_t word = apply_causal(read_word(slot), s_cur);
             const bool active = __ballot(word != 0) != 0;    // something visible for these 32 queries
             f32x16 sacc[2];
             if (active) qk_tile(Ks, sacc);
             if (SCHED && it + 1 < nt && s_nxt < 0) read_cols(slot ^ 1, gidx);
-            __syncthreads();                                 // K buffer and V buffer are free
+            __syncthreads();                                 // the K buffer is free
             if (it + 1 < nt) {
                 if (!SCHED || s_nxt >= 0) issue_tile_loads<D, NW, false>(k_rsrc, Ks, s_nxt, sk_bytes, wave, lane);
                 else issue_gather_loads<D, NW, false>(k_rsrc, Ks, gidx, sk_bytes, wave, lane);
             }
-            if (!SCHED || s_cur >= 0) issue_tile_loads<D, NW, true>(v_rsrc, Vs, s_cur, sv_bytes, wave, lane);
-            else issue_gather_loads<D, NW, true>(v_rsrc, Vs, gcur, sv_bytes, wave, lane);
-            if (it + 1 < nt) {
-                dma_words(it + 1, slot ^ 1);
-                s_cur = s_nxt;
-#pragma unroll
-                for (int u = 0; u < NLOAD; ++u) gcur[u] = gidx[u];
-                if (it + 2 < nt) {
-                    s_nxt = tile_start(it + 2);
-                    if (SCHED && s_nxt < 0) dma_cols(it + 2, slot);
-                }
-            }
             if (active) softmax_tile(word, sacc);
-            wait_vmem();                                     // V of this tile, K of the next, their metadata
+            // V of this tile has landed once at most the K loads just issued are outstanding
+            if (it + 1 < nt) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NLOAD) : "memory");
+            else wait_vmem();
             __syncthreads();
             if (active) pv_tile(Vs, sacc);
+            s_cur = s_nxt;
+            s_nxt = s_nn;
+#pragma unroll
+            for (int u = 0; u < NLOAD; ++u) gcur[u] = gidx[u];
         }
     }
 
