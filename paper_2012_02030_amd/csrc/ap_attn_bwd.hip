@@ -212,7 +212,10 @@ __global__ __launch_bounds__(256, 1) void bwd_dq_kernel(BwdArgs a, int nQB, int 
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int pos = 8 * (i / 4) + (i % 4);
-                    const float p = ((wbits[kb] >> pos) & 1u) ? __builtin_amdgcn_exp2f(fmaf(sacc[kb][i], sc, -lse2)) : 0.f;
+                    // pruned entries: the exponent's argument is replaced by -inf with a bit-select
+                    const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)wbits[kb], pos, 1);
+                    const float x = fmaf(sacc[kb][i], sc, -lse2);
+                    const float p = __builtin_amdgcn_exp2f(__uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep)));
                     sacc[kb][i] = p * (pacc[kb][i] - delta); // dS^T
                 }
             tr_mm_64<D>(lds + stage * STAGE + TILE, sacc, dqacc, tr);   // dQ^T += K^T dS^T

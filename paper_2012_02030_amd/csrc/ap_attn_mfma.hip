@@ -276,7 +276,10 @@ __global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int pos = 8 * (i / 4) + (i % 4);
-                    const float sv = ((wbits[kb] >> pos) & 1u) ? sacc[kb][i] : -INFINITY;
+                    // all-ones where kept (signed one-bit field), then a bit-select between the
+                    // score and -inf: two vector instructions and no condition code
+                    const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)wbits[kb], pos, 1);
+                    const float sv = __uint_as_float((__float_as_uint(sacc[kb][i]) & keep) | (0xff800000u & ~keep));
                     sacc[kb][i] = sv;
                     tmax = fmaxf(tmax, sv);
                 }
