@@ -17,6 +17,9 @@ kept_entry_flops   4*D flops per kept (query, key) connection: both N^2-sized pr
 The backward pass (gradients of the masked-attention equation) is in ``backward.py`` (numpy):
 masked_attention_backward.
 
+Masked attention with the 1.5-entmax normaliser of Section 6 is in ``entmax.py`` (numpy): entmax15,
+masked_entmax15_attention.
+
 Mask construction (Section 3.2, Eq. (1) and Eq. (2)) is in ``mask_construction.py`` (numpy):
 attention_maps, mean_attention_map, percentile_threshold, prune_mask.
 """
@@ -29,6 +32,7 @@ import subprocess
 import numpy as np
 
 from .backward import masked_attention_backward  # noqa: F401
+from .entmax import entmax15, masked_entmax15_attention  # noqa: F401
 from .mask_construction import (attention_maps, mean_attention_map,  # noqa: F401
                                 percentile_threshold, prune_mask)
 
