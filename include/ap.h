@@ -204,6 +204,34 @@ ap_status ap_sparse_attn_fwd_split(const void *Q, const void *K, const void *V, 
                                    void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Masked attention forward with the 1.5-entmax normaliser (Section 6: the experiments are repeated
+ * with 1.5-entmax in place of softmax, together with the pruning mask).
+ *
+ * For every batch b, head h and query i, over the keys j that ap_sparse_attn_fwd would use, with
+ * x_ij = scale * <Q[b,h,i,:], K[b,h,j,:]> / 2:
+ *
+ *     p_ij = max(x_ij - tau[b,h,i], 0)^2 ,  tau[b,h,i] such that sum_j p_ij = 1
+ *     O[b,h,i,:] = sum_j p_ij V[b,h,j,:]
+ *
+ * (the optimality conditions of 1.5-entmax; many p_ij are exactly 0).  tau is found by Newton's
+ * iteration to |sum_j p_ij - 1| <= 1e-5 and O is divided by the attained sum.  A query with no
+ * visible kept key gets O = 0 and tau = +infinity.
+ *
+ *   tau           out, float [B, H, Lq] contiguous, or NULL
+ *   everything else as in ap_sparse_attn_fwd (no schedule)
+ *
+ * Supported: dtype = AP_BF16, block_m = block_n = 64, D in {32, 64, 128}.  One launch; the tiles of
+ * a block row are swept several times (scores are recomputed, not stored).  Deterministic.
+ * ------------------------------------------------------------------------------------------- */
+ap_status ap_sparse_attn_entmax15_fwd(const void *Q, const void *K, const void *V, void *O, float *tau,
+                                      ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                      const int64_t *stride_q, const int64_t *stride_k,
+                                      const int64_t *stride_v, const int64_t *stride_o,
+                                      const int32_t *row_ptr, const int32_t *col_idx,
+                                      const uint64_t *bitmaps, int block_m, int block_n, int causal,
+                                      float softmax_scale, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Backward pass of masked attention (Section 3.2, algorithm step 4: the pruned model F' is
  * trained, which needs the gradients of the masked-attention equation).
  *

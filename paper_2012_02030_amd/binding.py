@@ -26,7 +26,7 @@ AP_BF16 = 1
 
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
            "ap_build_layout", "ap_build_schedule", "ap_sparse_attn_fwd",
-           "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
+           "ap_sparse_attn_entmax15_fwd", "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
            "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
            "ap_attention_maps_workspace_bytes", "ap_accumulate_attention_maps",
            "ap_prune_mask_workspace_bytes", "ap_prune_mask")
@@ -75,6 +75,11 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(i64), ctypes.POINTER(i64),
                                          vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
                                          ctypes.c_float, vp]
+        L.ap_sparse_attn_entmax15_fwd.restype = i32
+        L.ap_sparse_attn_entmax15_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                                  ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                                  ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                                  vp, vp, vp, i32, i32, i32, ctypes.c_float, vp]
         L.ap_fwd_split_workspace_bytes.restype = ctypes.c_size_t
         L.ap_fwd_split_workspace_bytes.argtypes = [i32] * 5
         L.ap_sparse_attn_fwd_split.restype = i32
@@ -260,6 +265,33 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_fwd")
     return out, lse
+
+
+def ap_sparse_attn_entmax15_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout: Layout,
+                                causal: bool = False, softmax_scale: float = 0.0,
+                                out: Optional[torch.Tensor] = None, return_tau: bool = True,
+                                stream: Optional[torch.cuda.Stream] = None):
+    """Masked attention with the 1.5-entmax normaliser (bf16, block_m 64).  Returns (O, tau)."""
+    if Q.dtype != torch.bfloat16 or K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise ValueError("Q, K, V must be bfloat16")
+    B, H, Lq, D = Q.shape
+    Lk = K.shape[2]
+    if tuple(K.shape) != (B, H, Lk, D) or tuple(V.shape) != (B, H, Lk, D):
+        raise ValueError("K/V shape mismatch")
+    if (H, Lq, Lk) != (layout.H, layout.Lq, layout.Lk):
+        raise ValueError("layout was built for other sizes")
+    if out is None:
+        out = torch.empty((B, H, Lq, D), dtype=Q.dtype, device=Q.device)
+    tau = torch.empty((B, H, Lq), dtype=torch.float32, device=Q.device) if return_tau else None
+    st = lib().ap_sparse_attn_entmax15_fwd(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+        tau.data_ptr() if tau is not None else None, AP_BF16, B, H, Lq, Lk, D,
+        _strides3(Q), _strides3(K), _strides3(V), _strides3(out),
+        layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
+        layout.block_m, layout.block_n, int(bool(causal)), float(softmax_scale), _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_sparse_attn_entmax15_fwd")
+    return out, tau
 
 
 def ap_fwd_split_workspace_bytes(B: int, H: int, Lq: int, D: int, splits: int) -> int:

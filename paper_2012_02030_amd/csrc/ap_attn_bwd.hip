@@ -78,16 +78,6 @@ __device__ __forceinline__ void merge_step(Merge& m, const int32_t* list)
     m.tb = (cb == m.key && cb != 0x7fffffff) ? m.ib++ : -1;
 }
 
-// One 512-byte block (64 x 8 bytes, or 128 x 4 bytes) into LDS by the first 32 lanes of a wavefront.
-__device__ __forceinline__ void dma_512(lds_u16* dst, const void* src_base, unsigned src_bytes, long long byte_off,
-                                        int lane)
-{
-    if (lane < 32) {
-        const rsrc_t rs = make_rsrc(src_base, src_bytes);
-        load16_to_lds(lds_addr_of(dst), lane * 16, rs, (int)byte_off);
-    }
-}
-
 // dQ: one workgroup per (example, head, pair of block rows); wavefronts 0,1 own the 64 queries of
 // the first block row, wavefronts 2,3 those of the second.  The tiles of both block rows are
 // walked together in ascending column order, so a K/V tile that both need is loaded once.  Two

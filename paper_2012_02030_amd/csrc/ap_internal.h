@@ -55,6 +55,9 @@ hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream);
 // same result, the entries of every block row cut into a.splits chunks and merged (block_m 64)
 hipError_t launch_fwd_split(const FwdArgs& a, hipStream_t stream);
 
+// ---- 1.5-entmax forward (ap_attn_entmax.hip): bf16, block 64x64, plain layout walk
+hipError_t launch_entmax15_fwd(const FwdArgs& a, float* tau_out, hipStream_t stream);
+
 // ---- backward pass (ap_layout_transpose.hip, ap_attn_bwd.hip)
 hipError_t launch_layout_transpose(const int32_t* row_ptr, const int32_t* col_idx, int H, int nQB,
                                    int nKB, long long cap, int32_t* col_ptr, int32_t* row_idx,

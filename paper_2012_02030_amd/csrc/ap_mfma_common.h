@@ -173,6 +173,16 @@ __device__ __forceinline__ int xcd_contiguous(int bid, int grid)
     return x * q + min(x, r) + (bid >> 3);
 }
 
+// One 512-byte block (64 x 8 bytes, or 128 x 4 bytes) into LDS by the first 32 lanes of a wavefront.
+__device__ __forceinline__ void dma_512(lds_u16* dst, const void* src_base, unsigned src_bytes, long long byte_off,
+                                        int lane)
+{
+    if (lane < 32) {
+        const rsrc_t rs = make_rsrc(src_base, src_bytes);
+        load16_to_lds(lds_addr_of(dst), lane * 16, rs, (int)byte_off);
+    }
+}
+
 // Per-lane constants of the transposing LDS reads of a 64-row tile stored with the value swizzle.
 struct TrRead {
     int lane_row, in_chunk, chunk_lo, swz;

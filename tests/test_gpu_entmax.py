@@ -1,0 +1,74 @@
+"""GPU parity of masked attention with the 1.5-entmax normaliser (Section 6) against the fp64
+oracle: O within the forward tolerance (bf16 inputs and output, P rounded to bf16 before the
+second product), tau within 1e-3 (Newton's iteration stops at |sum p - 1| <= 1e-5, scores in fp32)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2012_02030_amd import binding as ap
+from paper_2012_02030_amd import synth
+
+from gpu_util import TOL, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def run_entmax(Q, K, V, mask, causal, scale=0.0):
+    dq, rq = to_device(Q, "bf16")
+    dk, rk = to_device(K, "bf16")
+    dv, rv = to_device(V, "bf16")
+    lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
+    O, tau = ap.ap_sparse_attn_entmax15_fwd(dq, dk, dv, lay, causal=causal, softmax_scale=scale)
+    torch.cuda.synchronize()
+    O_ref, tau_ref = oracle.masked_entmax15_attention(rq, rk, rv, mask, causal=causal, scale=scale)
+    Oh, th = O.double().cpu().numpy(), tau.double().cpu().numpy()
+    assert np.isfinite(Oh).all()
+    err = float(np.abs(Oh - O_ref).max())
+    assert err <= TOL["bf16"], "max |O - oracle| = %.3e" % err
+    empty = np.isinf(tau_ref)
+    assert np.array_equal(np.isinf(th), empty)
+    if (~empty).any():
+        terr = float(np.abs(th[~empty] - tau_ref[~empty]).max())
+        assert terr <= 1e-3, "max |tau - oracle| = %.3e" % terr
+    return err
+
+
+def rand_qkv(seed, B, H, Lq, Lk, D, gain=1.0):
+    rng = np.random.default_rng([synth.SEED, 1515, seed])
+    return (gain * rng.standard_normal((B, H, Lq, D), dtype=np.float32),
+            rng.standard_normal((B, H, Lk, D), dtype=np.float32),
+            rng.standard_normal((B, H, Lk, D), dtype=np.float32))
+
+
+ENTMAX_CASES = [
+    # B, H, Lq, Lk, D, causal, density, query gain (sharper scores -> smaller supports)
+    (2, 2, 128, 128, 64, False, 0.5, 1.0),
+    (1, 2, 200, 200, 64, True, 0.3, 3.0),
+    (1, 2, 100, 157, 32, False, 0.3, 1.0),
+    (1, 2, 100, 300, 128, True, 0.2, 0.2),      # nearly equal scores: large supports
+    (1, 1, 192, 192, 128, False, 1.0, 1.0),     # nothing pruned
+    (1, 2, 64, 64, 64, True, 0.05, 1.0),        # empty rows
+    (1, 1, 1, 1, 32, False, 1.0, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", ENTMAX_CASES, ids=lambda c: "B%d_H%d_%dx%d_D%d_%s_g%g" % (c[:5] + ("causal" if c[5] else "full", c[7])))
+def test_entmax_forward_matches_oracle(case):
+    B, H, Lq, Lk, D, causal, density, gain = case
+    Q, K, V = rand_qkv(Lq + Lk + D, B, H, Lq, Lk, D, gain)
+    mask = synth.random_mask(H, Lq, Lk, density, seed=Lq + D)
+    run_entmax(Q, K, V, mask, causal)
+
+
+def test_entmax_zero_queries_give_the_mean_of_kept_values():
+    Q, K, V = rand_qkv(3, 1, 2, 96, 96, 64)
+    mask = synth.random_mask(2, 96, 96, 0.4, seed=8)
+    run_entmax(0.0 * Q, K, V, mask, False)
+
+
+def test_entmax_on_a_structured_mask_and_explicit_scale():
+    cfg = synth.CONFIGS["C3"]
+    mask = np.stack([synth.head_mask(cfg, h) for h in range(2)]).astype(np.uint8)
+    Q, K, V = rand_qkv(5, 1, 2, cfg.Lq, cfg.Lk, cfg.D, 2.0)
+    run_entmax(Q, K, V, mask, True, scale=0.2)
