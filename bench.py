@@ -39,6 +39,8 @@ def parse():
     p.add_argument("--no-sched", action="store_true", help="walk the layout itself instead of the visit schedule")
     p.add_argument("--only", action="store_true", help="skip the per-config table and the CPU baseline")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    p.add_argument("--only-entmax", action="store_true",
+                   help="time only the 1.5-entmax forward at the workload's shape and print its figures")
     p.add_argument("--only-split", action="store_true",
                    help="time only the split forward call on the long-memory shape X1 and print its figures")
     p.add_argument("--only-backward", action="store_true",
@@ -468,6 +470,48 @@ def main():
             "hbm_roofline_frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         }
 
+    def run_entmax(cfg, mask_np, steps):
+        """1.5-entmax forward of cfg under its AP mask (plain layout walk) next to the softmax
+        forward over the same layout walk."""
+        if cfg.dtype != "bf16":
+            return None
+        lay = ap.ap_build_layout(torch.from_numpy(mask_np).to(dev), 64, 64)
+        q, k, v = (torch.from_numpy(x).to(torch.bfloat16).to(dev) for x in synth.make_qkv(cfg))
+        out = torch.empty_like(q)
+
+        def timed(fn, n):
+            fn()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            torch.cuda.synchronize()
+            evs[0].record()
+            for i in range(n):
+                fn()
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            return float(np.mean([evs[i].elapsed_time(evs[i + 1]) for i in range(n)]))
+
+        ent_ms = timed(lambda: ap.ap_sparse_attn_entmax15_fwd(q, k, v, lay, causal=cfg.causal, out=out), steps)
+        soft_ms = timed(lambda: ap.ap_sparse_attn_fwd(q, k, v, lay, causal=cfg.causal, out=out), steps)
+        O, tau = ap.ap_sparse_attn_entmax15_fwd(q, k, v, lay, causal=cfg.causal)
+        kept = int(mask_np.sum())
+        tiles = int(lay.nnz.item())
+        return {
+            "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D, "causal": cfg.causal},
+            "tiles_walked": tiles,
+            "entmax_ms": ent_ms,
+            "softmax_same_walk_ms": soft_ms,
+            "ratio_to_softmax": ent_ms / soft_ms,
+            "kept_tflops": 4.0 * cfg.D * kept * cfg.B / (ent_ms * 1e-3) / 1e12,
+            "hbm_alg_bytes": alg_bytes(cfg),
+            "hbm_gbs": alg_bytes(cfg) / (ent_ms * 1e-3) / 1e9,
+            "hbm_roofline_frac": alg_bytes(cfg) / (ent_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        }
+
+    if args.only_entmax:
+        cfg = synth.CONFIGS[args.workload]
+        print(json.dumps({"entmax15_forward": run_entmax(cfg, synth.make_mask(cfg), args.steps)}), flush=True)
+        return
+
     if args.only_split:
         print(json.dumps({"split_forward": run_split_forward(synth.EXTRA_CONFIGS["X1"], args.steps)}), flush=True)
         return
@@ -554,6 +598,12 @@ def main():
         split_forward = run_split_forward(synth.EXTRA_CONFIGS["X1"], 20)
         torch.cuda.empty_cache()
 
+    entmax = None
+    if not args.only:
+        log("timing the 1.5-entmax forward at the", head.name, "shape ...")
+        entmax = run_entmax(head, head_mask, 10)
+        torch.cuda.empty_cache()
+
     backward = None
     if not args.only and not args.no_backward:
         log("timing the backward pass at the", head.name, "shape ...")
@@ -598,6 +648,7 @@ def main():
         "mask_construction": mask_construction,
         "backward": backward,
         "split_forward": split_forward,
+        "entmax15_forward": entmax,
         "per_config": per_config,
     }
     print(json.dumps(out), flush=True)

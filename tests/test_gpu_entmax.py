@@ -72,3 +72,31 @@ def test_entmax_on_a_structured_mask_and_explicit_scale():
     mask = np.stack([synth.head_mask(cfg, h) for h in range(2)]).astype(np.uint8)
     Q, K, V = rand_qkv(5, 1, 2, cfg.Lq, cfg.Lk, cfg.D, 2.0)
     run_entmax(Q, K, V, mask, True, scale=0.2)
+
+
+def test_entmax_full_size_c5_two_slices_against_oracle():
+    """The benchmark's shape (B4 H16 L4096 D128 causal, C5's mask): two (example, head) slices
+    element by element, and the rows of every slice are finite."""
+    cfg = synth.CONFIGS["C5"]
+    mask = synth.make_mask(cfg)
+    Q, K, V = synth.make_qkv(cfg)
+    dq, dk, dv = (torch.from_numpy(x).to(torch.bfloat16).cuda() for x in (Q, K, V))
+    lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
+    O, tau = ap.ap_sparse_attn_entmax15_fwd(dq, dk, dv, lay, causal=True)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O).all()) and bool(torch.isfinite(tau).all())
+    for b, h in ((0, 1), (3, 14)):
+        sl = lambda t: t[b:b + 1, h:h + 1].double().cpu().numpy()
+        rows = slice(0, cfg.Lq, 7)                               # every 7th query keeps the oracle quick
+        O_ref, tau_ref = oracle.masked_entmax15_attention(sl(dq)[:, :, rows], sl(dk), sl(dv),
+                                                          _rows_mask(mask[h:h + 1], rows, cfg), causal=False)
+        assert np.abs(sl(O)[:, :, rows] - O_ref).max() <= TOL["bf16"]
+        assert np.abs(sl(tau)[:, :, rows] - tau_ref).max() <= 1e-3
+
+
+def _rows_mask(mask_h, rows, cfg):
+    """Mask rows of the sampled queries with the causal limit folded in (the oracle is then called
+    without its causal flag, which would align a query subset differently)."""
+    i = np.arange(cfg.Lq)[rows][:, None]
+    j = np.arange(cfg.Lk)[None, :]
+    return (mask_h[:, rows, :] != 0) & (j <= i + (cfg.Lk - cfg.Lq))[None]
