@@ -490,15 +490,19 @@ def main():
             torch.cuda.synchronize()
             return float(np.mean([evs[i].elapsed_time(evs[i + 1]) for i in range(n)]))
 
-        ent_ms = timed(lambda: ap.ap_sparse_attn_entmax15_fwd(q, k, v, lay, causal=cfg.causal, out=out), steps)
-        soft_ms = timed(lambda: ap.ap_sparse_attn_fwd(q, k, v, lay, causal=cfg.causal, out=out), steps)
-        O, tau = ap.ap_sparse_attn_entmax15_fwd(q, k, v, lay, causal=cfg.causal)
+        sched = ap.ap_build_schedule(lay, causal=cfg.causal, min_cols=args.min_cols)
+        walk_ms = timed(lambda: ap.ap_sparse_attn_entmax15_fwd(q, k, v, lay, causal=cfg.causal, out=out), steps)
+        ent_ms = timed(lambda: ap.ap_sparse_attn_entmax15_fwd(q, k, v, lay, causal=cfg.causal, out=out,
+                                                               sched=sched), steps)
+        soft_ms = timed(lambda: ap.ap_sparse_attn_fwd(q, k, v, lay, causal=cfg.causal, out=out, sched=sched), steps)
         kept = int(mask_np.sum())
         tiles = int(lay.nnz.item())
         return {
             "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D, "causal": cfg.causal},
-            "tiles_walked": tiles,
+            "tiles_stored": tiles,
+            "entries_visited": int(sched.cnt.sum().item()),
             "entmax_ms": ent_ms,
+            "entmax_layout_walk_ms": walk_ms,
             "softmax_same_walk_ms": soft_ms,
             "ratio_to_softmax": ent_ms / soft_ms,
             "kept_tflops": 4.0 * cfg.D * kept * cfg.B / (ent_ms * 1e-3) / 1e12,

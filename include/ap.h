@@ -218,7 +218,8 @@ ap_status ap_sparse_attn_fwd_split(const void *Q, const void *K, const void *V, 
  * visible kept key gets O = 0 and tau = +infinity.
  *
  *   tau           out, float [B, H, Lq] contiguous, or NULL
- *   everything else as in ap_sparse_attn_fwd (no schedule)
+ *   everything else as in ap_sparse_attn_fwd; a block row with more than 64 schedule entries
+ *   walks the layout's tiles instead (same result)
  *
  * Supported: dtype = AP_BF16, block_m = block_n = 64, D in {32, 64, 128}.  One launch; the tiles of
  * a block row are swept several times (scores are recomputed, not stored).  Deterministic.
@@ -228,8 +229,9 @@ ap_status ap_sparse_attn_entmax15_fwd(const void *Q, const void *K, const void *
                                       const int64_t *stride_q, const int64_t *stride_k,
                                       const int64_t *stride_v, const int64_t *stride_o,
                                       const int32_t *row_ptr, const int32_t *col_idx,
-                                      const uint64_t *bitmaps, int block_m, int block_n, int causal,
-                                      float softmax_scale, void *stream);
+                                      const uint64_t *bitmaps, int block_m, int block_n,
+                                      const ap_schedule *sched, int causal, float softmax_scale,
+                                      void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Backward pass of masked attention (Section 3.2, algorithm step 4: the pruned model F' is

@@ -79,7 +79,8 @@ def lib() -> ctypes.CDLL:
         L.ap_sparse_attn_entmax15_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
                                                   ctypes.POINTER(i64), ctypes.POINTER(i64),
                                                   ctypes.POINTER(i64), ctypes.POINTER(i64),
-                                                  vp, vp, vp, i32, i32, i32, ctypes.c_float, vp]
+                                                  vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
+                                                  ctypes.c_float, vp]
         L.ap_fwd_split_workspace_bytes.restype = ctypes.c_size_t
         L.ap_fwd_split_workspace_bytes.argtypes = [i32] * 5
         L.ap_sparse_attn_fwd_split.restype = i32
@@ -270,8 +271,12 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
 def ap_sparse_attn_entmax15_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout: Layout,
                                 causal: bool = False, softmax_scale: float = 0.0,
                                 out: Optional[torch.Tensor] = None, return_tau: bool = True,
-                                stream: Optional[torch.cuda.Stream] = None):
+                                stream: Optional[torch.cuda.Stream] = None,
+                                sched: Optional[Schedule] = None):
     """Masked attention with the 1.5-entmax normaliser (bf16, block_m 64).  Returns (O, tau)."""
+    if sched is not None and sched.causal != bool(causal):
+        raise ValueError("schedule was built with causal=%s" % sched.causal)
+    cs = sched.c_struct() if sched is not None else None
     if Q.dtype != torch.bfloat16 or K.dtype != Q.dtype or V.dtype != Q.dtype:
         raise ValueError("Q, K, V must be bfloat16")
     B, H, Lq, D = Q.shape
@@ -288,7 +293,8 @@ def ap_sparse_attn_entmax15_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tenso
         tau.data_ptr() if tau is not None else None, AP_BF16, B, H, Lq, Lk, D,
         _strides3(Q), _strides3(K), _strides3(V), _strides3(out),
         layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
-        layout.block_m, layout.block_n, int(bool(causal)), float(softmax_scale), _stream_ptr(stream))
+        layout.block_m, layout.block_n, ctypes.byref(cs) if cs is not None else None,
+        int(bool(causal)), float(softmax_scale), _stream_ptr(stream))
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_entmax15_fwd")
     return out, tau

@@ -141,7 +141,7 @@ static ap_status fwd_common(const void* Q, const void* K, const void* V, void* O
                              (long long)Lk * stride_v[2] * 2 >= 2147483647LL))
         return AP_ERR_UNSUPPORTED;
 
-    if (entmax && (dtype != AP_BF16 || block_m != 64 || sched)) return AP_ERR_UNSUPPORTED;
+    if (entmax && (dtype != AP_BF16 || block_m != 64)) return AP_ERR_UNSUPPORTED;
     // bitmap rows are fetched with 32-bit byte offsets there: 512 bytes per tile
     if (entmax && nQB * ((Lk + 63) / 64) * H >= (1LL << 22)) return AP_ERR_UNSUPPORTED;
     if (splits > 0) {
@@ -199,11 +199,12 @@ ap_status ap_sparse_attn_entmax15_fwd(const void* Q, const void* K, const void* 
                                       const int64_t* stride_q, const int64_t* stride_k,
                                       const int64_t* stride_v, const int64_t* stride_o,
                                       const int32_t* row_ptr, const int32_t* col_idx,
-                                      const uint64_t* bitmaps, int block_m, int block_n, int causal,
-                                      float softmax_scale, void* stream)
+                                      const uint64_t* bitmaps, int block_m, int block_n,
+                                      const ap_schedule* sched, int causal, float softmax_scale,
+                                      void* stream)
 {
     return fwd_common(Q, K, V, O, tau, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v, stride_o,
-                      row_ptr, col_idx, bitmaps, block_m, block_n, nullptr, causal, softmax_scale, 0,
+                      row_ptr, col_idx, bitmaps, block_m, block_n, sched, causal, softmax_scale, 0,
                       nullptr, 0, stream, true);
 }
 

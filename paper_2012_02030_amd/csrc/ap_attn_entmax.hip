@@ -17,8 +17,8 @@
 //               the sweeps.  The block row iterates until every row has | |d|^2 - 1 | <= 1e-5.
 //   last sweep  P = [y - tau]_+^2, O^T += V^T P^T, O / sum P.
 //
-// Same operand layouts, LDS swizzles and LDS-direct loads as the softmax kernel; plain layout
-// walk, 64x64 tiles, two LDS stages of K (one barrier per tile) in the threshold sweeps.
+// Same operand layouts, LDS swizzles and LDS-direct loads as the softmax kernel; walks the
+// layout's tiles or, if given, the entries of its visit schedule; 64x64 tiles, two LDS stages of K (one barrier per tile) in the threshold sweeps.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -33,6 +33,7 @@ using namespace mfma;
 
 constexpr float kEntmaxTol = 1e-5f;          // on sum p - 1
 constexpr int kEntmaxMaxIter = 60;
+constexpr int kEntmaxSchedEntries = 64;      // a block row with more schedule entries walks the layout instead
 
 template <int D>
 __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* tau_out, int nQB)
@@ -41,7 +42,10 @@ __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* 
     constexpr int KSTEPS = D / 16;
     constexpr int DBLK = D / 32;
     constexpr int STAGE = TILE + 256;                        // a K (or V) tile and 64 bitmap words
+    constexpr int RPI = 64 / (D / 8);                        // tile rows per load instruction
+    constexpr int NLOAD = (D / 8) / 2;                       // load instructions per wavefront and tile
     __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * STAGE];
+    __shared__ int32_t s_cols[kEntmaxSchedEntries][64];      // gather keys of the block row's entries
     lds_u16* lds = (lds_u16*)smem;
 
     const int tid = threadIdx.x;
@@ -81,10 +85,20 @@ __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* 
     const int r = h * nQB + qb;
     const int t0 = a.row_ptr[r];
     int t1 = a.row_ptr[r + 1];
-    if (a.causal) {                                          // columns ascend: hidden tiles are at the end
+    // With a visit schedule the entries of the block row replace its tiles: runs of 64 consecutive
+    // keys or 64 gathered keys, causal limit already folded into their bitmaps.  The gather keys
+    // are read every sweep, so they are copied to LDS once.
+    const bool use_sched = a.sched.cnt != nullptr && a.sched.cnt[r] <= kEntmaxSchedEntries;
+    if (use_sched) {
+        t1 = t0 + a.sched.cnt[r];
+        for (int i = tid; i < (t1 - t0) * 64; i += 128)
+            s_cols[i >> 6][i & 63] = a.sched.start[t0 + (i >> 6)] < 0 ? a.sched.cols[(size_t)t0 * 64 + i] : 0;
+    } else if (a.causal) {                                   // columns ascend: hidden tiles are at the end
         while (t1 > t0 && (long long)a.col_idx[t1 - 1] * kBN > block_diag) --t1;
     }
+    const uint64_t* words = use_sched ? a.sched.bitmaps : a.bitmaps;
     const unsigned words_bytes = (unsigned)a.row_ptr[r + 1] * 512u;
+    const int g_row = lane / (D / 8);
 
     wait_vmem();
     settle<KSTEPS>(qreg);
@@ -102,10 +116,18 @@ __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* 
         // with V (last sweep only): K in the first buffer, V in the second, loaded per tile.
         auto issue = [&](int t, int stage) {
             lds_u16* base = lds + stage * STAGE;
-            const int k0 = a.col_idx[t] * kBN;
-            issue_tile_loads<D, 2, false>(k_rsrc, base, k0, sk_bytes, wave, lane);
-            if (with_v) issue_tile_loads<D, 2, true>(v_rsrc, lds + STAGE, k0, sv_bytes, wave, lane);
-            if (wave == 0) dma_512(base + TILE, a.bitmaps, words_bytes, (long long)t * 512, lane);
+            const int k0 = use_sched ? a.sched.start[t] : a.col_idx[t] * kBN;
+            if (k0 >= 0) {
+                issue_tile_loads<D, 2, false>(k_rsrc, base, k0, sk_bytes, wave, lane);
+                if (with_v) issue_tile_loads<D, 2, true>(v_rsrc, lds + STAGE, k0, sv_bytes, wave, lane);
+            } else {                                         // gathered entry: an empty slot holds Lk (reads zeros)
+                int gk[NLOAD];
+#pragma unroll
+                for (int u = 0; u < NLOAD; ++u) gk[u] = s_cols[t - t0][(wave + 2 * u) * RPI + g_row];
+                issue_gather_loads<D, 2, false>(k_rsrc, base, gk, sk_bytes, wave, lane);
+                if (with_v) issue_gather_loads<D, 2, true>(v_rsrc, lds + STAGE, gk, sv_bytes, wave, lane);
+            }
+            if (wave == 0) dma_512(base + TILE, words, words_bytes, (long long)t * 512, lane);
         };
         __syncthreads();                                     // the previous sweep is done with both buffers
         if (!with_v && t0 < t1) issue(t0, 0);
@@ -120,7 +142,7 @@ __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* 
             if (!with_v && t + 1 < t1) issue(t + 1, stage ^ 1);
             uint16_t* base = smem + stage * STAGE;
             uint64_t word = *reinterpret_cast<const uint64_t*>(base + TILE + brow * 4);
-            if (a.causal) {
+            if (a.causal && !use_sched) {
                 const long long lim = diag - (long long)a.col_idx[t] * kBN;
                 if (lim < 0) word = 0;
                 else if (lim < 63) word &= (2ull << lim) - 1ull;

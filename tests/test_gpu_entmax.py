@@ -15,13 +15,22 @@ pytestmark = pytest.mark.gpu
 
 
 def run_entmax(Q, K, V, mask, causal, scale=0.0):
+    """Both walks (layout tiles, visit schedule) against the oracle."""
     dq, rq = to_device(Q, "bf16")
     dk, rk = to_device(K, "bf16")
     dv, rv = to_device(V, "bf16")
     lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
-    O, tau = ap.ap_sparse_attn_entmax15_fwd(dq, dk, dv, lay, causal=causal, softmax_scale=scale)
-    torch.cuda.synchronize()
+    sched = ap.ap_build_schedule(lay, causal=causal)
     O_ref, tau_ref = oracle.masked_entmax15_attention(rq, rk, rv, mask, causal=causal, scale=scale)
+    err = 0.0
+    for sc in (None, sched):
+        O, tau = ap.ap_sparse_attn_entmax15_fwd(dq, dk, dv, lay, causal=causal, softmax_scale=scale, sched=sc)
+        torch.cuda.synchronize()
+        err = max(err, check_entmax(O, tau, O_ref, tau_ref))
+    return err
+
+
+def check_entmax(O, tau, O_ref, tau_ref):
     Oh, th = O.double().cpu().numpy(), tau.double().cpu().numpy()
     assert np.isfinite(Oh).all()
     err = float(np.abs(Oh - O_ref).max())
@@ -82,7 +91,8 @@ def test_entmax_full_size_c5_two_slices_against_oracle():
     Q, K, V = synth.make_qkv(cfg)
     dq, dk, dv = (torch.from_numpy(x).to(torch.bfloat16).cuda() for x in (Q, K, V))
     lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
-    O, tau = ap.ap_sparse_attn_entmax15_fwd(dq, dk, dv, lay, causal=True)
+    sched = ap.ap_build_schedule(lay, causal=True)
+    O, tau = ap.ap_sparse_attn_entmax15_fwd(dq, dk, dv, lay, causal=True, sched=sched)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(O).all()) and bool(torch.isfinite(tau).all())
     for b, h in ((0, 1), (3, 14)):
@@ -100,3 +110,11 @@ def _rows_mask(mask_h, rows, cfg):
     i = np.arange(cfg.Lq)[rows][:, None]
     j = np.arange(cfg.Lk)[None, :]
     return (mask_h[:, rows, :] != 0) & (j <= i + (cfg.Lk - cfg.Lq))[None]
+
+
+def test_entmax_block_row_with_more_than_64_schedule_entries():
+    """Dense 64 x 5000 mask: 79 consecutive entries in the one block row, more than the kernel
+    keeps gather keys for, so it walks the layout's tiles."""
+    Q, K, V = rand_qkv(11, 1, 1, 64, 5000, 64)
+    mask = np.ones((1, 64, 5000), np.uint8)
+    run_entmax(Q, K, V, mask, False)
