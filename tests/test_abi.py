@@ -193,6 +193,28 @@ def test_split_forward_arguments(L):
     assert call(sq=bad) == ap.AP_ERR_INVALID_ARG
 
 
+def test_entmax_forward_arguments(L):
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+
+    def call(**over):
+        a = dict(Q=fake, K=fake + 0x100000, V=fake + 0x200000, O=fake + 0x300000, dtype=ap.AP_BF16, bm=64, D=64,
+                 causal=0, Lq=64, Lk=64, sched=None)
+        a.update(over)
+        return L.ap_sparse_attn_entmax15_fwd(a["Q"], a["K"], a["V"], a["O"], None, a["dtype"], 1, 2, a["Lq"],
+                                             a["Lk"], a["D"], s, s, s, s, fake, fake, fake, a["bm"], 64,
+                                             a["sched"], a["causal"], 0.0, None)
+
+    assert call(K=None) == ap.AP_ERR_INVALID_ARG
+    assert call(dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    assert call(bm=128) == ap.AP_ERR_UNSUPPORTED
+    assert call(D=48) == ap.AP_ERR_UNSUPPORTED
+    assert call(causal=1, Lq=128, Lk=64) == ap.AP_ERR_INVALID_ARG
+    assert call(O=fake) == ap.AP_ERR_INVALID_ARG
+    hole = ap._CSchedule(fake, None, fake, fake)
+    assert call(sched=ctypes.pointer(hole)) == ap.AP_ERR_INVALID_ARG
+
+
 def test_backward_arguments(L):
     fake = 0x1000
     s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
