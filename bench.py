@@ -405,6 +405,13 @@ def main():
 
         bwd_ms = timed(lambda: ap.ap_sparse_attn_bwd(q, k, v, O, g, lse, lay, lt, causal=cfg.causal), steps)
         tr_ms = timed(lambda: ap.ap_build_layout_transpose(lay), steps)
+        rs = ap.ap_build_schedule(lay, causal=cfg.causal, min_cols=args.min_cols)
+        cs = ap.ap_build_col_schedule(lay, lt, causal=cfg.causal)
+        sched_ms = timed(lambda: ap.ap_sparse_attn_bwd(q, k, v, O, g, lse, lay, lt, causal=cfg.causal,
+                                                       sched=rs, col_sched=cs), steps)
+        cs_ms = timed(lambda: ap.ap_build_col_schedule(lay, lt, causal=cfg.causal), steps)
+        row_entries = int(rs.cnt.sum().item())
+        col_entries = int(cs.cnt.sum().item())
         kept = int(mask_np.sum())
         kept_flop = 10.0 * cfg.D * kept * cfg.B               # five N^2-sized products per kept entry
         tiles = int(lay.nnz.item())
@@ -421,6 +428,17 @@ def main():
             "hbm_alg_bytes": alg,
             "hbm_gbs": alg / (bwd_ms * 1e-3) / 1e9,
             "layout_transpose_ms": tr_ms,
+            "scheduled": {
+                "bwd_ms": sched_ms,
+                "row_entries": row_entries,
+                "col_entries": col_entries,
+                "kept_tflops": kept_flop / (sched_ms * 1e-3) / 1e12,
+                "entry_mfma_tflops": 64 * 64 * cfg.D * cfg.B * (6.0 * row_entries + 8.0 * col_entries)
+                                     / (sched_ms * 1e-3) / 1e12,
+                "hbm_gbs": alg / (sched_ms * 1e-3) / 1e9,
+                "col_schedule_ms": cs_ms,
+                "speedup_vs_layout_walk": bwd_ms / sched_ms,
+            },
         }
 
     def run_split_forward(cfg, steps):

@@ -286,6 +286,48 @@ ap_status ap_sparse_attn_bwd(const void *Q, const void *K, const void *V, const 
                              size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Backward pass over visit schedules: the same gradients as ap_sparse_attn_bwd (same passage of
+ * the paper), skipping what the scheduled forward pass skips.
+ *
+ * dQ walks the row schedule of ap_build_schedule (entries of 64 consecutive or 64 gathered keys
+ * per block row).  dK and dV walk a column schedule, the same structure with rows and columns
+ * swapped, built from the transposed layout by ap_build_col_schedule: entry e of block column c
+ * is element col_ptr[c] + e of its arrays;
+ *     cnt   [H * ceil(Lk/64)]  entries of each block column
+ *     start [cap]              >= 0: first query of 64 consecutive queries; -1: gathered queries
+ *     cols  [cap*64]           query index per slot of a gathered entry; empty slots hold Lq
+ *     bitmaps [cap*64]         per query slot: bit c set = key 64*kb + c kept and visible
+ * A stored tile in which at least min_rows query rows hold a visible kept entry stays one entry of
+ * consecutive queries; the rows of the other tiles that hold one are packed, in ascending order,
+ * into gathered entries.  min_rows in [1, 65]: 1 keeps every tile with a visible entry as it is,
+ * 65 gathers everything; 0 selects the default.  Tiles without a visible kept entry are dropped.
+ *
+ * ap_sparse_attn_bwd_sched takes the arguments of ap_sparse_attn_bwd plus
+ *   sched         NULL (dQ walks the layout's tiles), or the row schedule built from this layout
+ *                 with the same `causal`
+ *   col_sched     NULL (dK, dV walk the transposed layout), or the column schedule built from
+ *                 this layout's transpose with the same `causal`
+ * Same support, same determinism; results differ from ap_sparse_attn_bwd only by the order of
+ * the fp32 sums.
+ * ------------------------------------------------------------------------------------------- */
+ap_status ap_build_col_schedule(const int32_t *col_ptr, const int32_t *row_idx, const int32_t *tile_idx,
+                                const uint64_t *bitmaps, int H, int Lq, int Lk, int block_m,
+                                int block_n, int64_t cap, int causal, int min_rows,
+                                const ap_schedule *col_sched, void *stream);
+
+ap_status ap_sparse_attn_bwd_sched(const void *Q, const void *K, const void *V, const void *O,
+                                   const void *dO, const float *lse, void *dQ, void *dK, void *dV,
+                                   ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                   const int64_t *stride_q, const int64_t *stride_k,
+                                   const int64_t *stride_v, const int64_t *stride_o,
+                                   const int32_t *row_ptr, const int32_t *col_idx,
+                                   const uint64_t *bitmaps, const int32_t *col_ptr,
+                                   const int32_t *row_idx, const int32_t *tile_idx, int block_m,
+                                   int block_n, const ap_schedule *sched,
+                                   const ap_schedule *col_sched, int causal, float softmax_scale,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Mask construction, step 1: accumulate attention matrices into the mean map (Section 3.2,
  * Eq. (1)).
  *

@@ -28,6 +28,7 @@ SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes
            "ap_build_layout", "ap_build_schedule", "ap_sparse_attn_fwd",
            "ap_sparse_attn_entmax15_fwd", "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
            "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
+           "ap_build_col_schedule", "ap_sparse_attn_bwd_sched",
            "ap_attention_maps_workspace_bytes", "ap_accumulate_attention_maps",
            "ap_prune_mask_workspace_bytes", "ap_prune_mask")
 
@@ -96,6 +97,13 @@ def lib() -> ctypes.CDLL:
         L.ap_sparse_attn_bwd.restype = i32
         L.ap_sparse_attn_bwd.argtypes = [vp] * 9 + [i32] * 6 + [ctypes.POINTER(i64)] * 4 + [vp] * 6 + \
                                         [i32, i32, i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
+        L.ap_build_col_schedule.restype = i32
+        L.ap_build_col_schedule.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i64, i32, i32,
+                                            ctypes.POINTER(_CSchedule), vp]
+        L.ap_sparse_attn_bwd_sched.restype = i32
+        L.ap_sparse_attn_bwd_sched.argtypes = [vp] * 9 + [i32] * 6 + [ctypes.POINTER(i64)] * 4 + [vp] * 6 + \
+                                              [i32, i32, ctypes.POINTER(_CSchedule), ctypes.POINTER(_CSchedule),
+                                               i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
         L.ap_attention_maps_workspace_bytes.restype = ctypes.c_size_t
         L.ap_attention_maps_workspace_bytes.argtypes = [i32] * 3
         L.ap_accumulate_attention_maps.restype = i32
@@ -368,13 +376,39 @@ def ap_bwd_workspace_bytes(B: int, H: int, Lq: int) -> int:
     return int(lib().ap_bwd_workspace_bytes(B, H, Lq))
 
 
+def ap_build_col_schedule(layout: Layout, layout_t: LayoutT, causal: bool = False, min_rows: int = 0,
+                          stream: Optional[torch.cuda.Stream] = None) -> Schedule:
+    """Derive the column schedule (for dK, dV) from a layout and its transpose.  Asynchronous."""
+    dev = layout.row_ptr.device
+    cap = int(layout.col_idx.shape[0])
+    ncols = int(layout_t.col_ptr.shape[0]) - 1
+    sched = Schedule(torch.empty(ncols, dtype=torch.int32, device=dev),
+                     torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
+                     torch.empty((max(cap, 1), 64), dtype=torch.int32, device=dev),
+                     torch.empty((max(cap, 1), 64), dtype=torch.int64, device=dev),
+                     bool(causal), int(min_rows))
+    cs = sched.c_struct()
+    st = lib().ap_build_col_schedule(layout_t.col_ptr.data_ptr(), layout_t.row_idx.data_ptr(),
+                                     layout_t.tile_idx.data_ptr(), layout.bitmaps.data_ptr(), layout.H,
+                                     layout.Lq, layout.Lk, layout.block_m, layout.block_n, cap,
+                                     int(bool(causal)), int(min_rows), ctypes.byref(cs), _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_build_col_schedule")
+    return sched
+
+
 def ap_sparse_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: torch.Tensor,
                        dO: torch.Tensor, lse: torch.Tensor, layout: Layout, layout_t: LayoutT,
                        causal: bool = False, softmax_scale: float = 0.0,
-                       stream: Optional[torch.cuda.Stream] = None):
+                       stream: Optional[torch.cuda.Stream] = None,
+                       sched: Optional[Schedule] = None, col_sched: Optional[Schedule] = None):
     """Gradients (dQ, dK, dV) of ap_sparse_attn_fwd's O with respect to Q, K, V (bf16).
 
-    O and lse are the forward call's outputs; dO must have O's strides.  Asynchronous on the stream."""
+    O and lse are the forward call's outputs; dO must have O's strides.  With a row schedule
+    and/or a column schedule the call goes to ap_sparse_attn_bwd_sched.  Asynchronous on the stream."""
+    for sc in (sched, col_sched):
+        if sc is not None and sc.causal != bool(causal):
+            raise ValueError("schedule was built with another `causal`")
     for t in (Q, K, V, O, dO):
         if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1:
             raise ValueError("Q, K, V, O, dO must be bfloat16 [B, H, L, D] with a contiguous last dimension")
@@ -395,14 +429,20 @@ def ap_sparse_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: tor
     dV = torch.empty_strided(V.shape, V.stride(), dtype=V.dtype, device=V.device)
     ws_bytes = ap_bwd_workspace_bytes(B, H, Lq)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=Q.device)
-    st = lib().ap_sparse_attn_bwd(
-        Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), lse.data_ptr(),
-        dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), AP_BF16, B, H, Lq, Lk, D,
-        _strides3(Q), _strides3(K), _strides3(V), _strides3(O),
-        layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
-        layout_t.col_ptr.data_ptr(), layout_t.row_idx.data_ptr(), layout_t.tile_idx.data_ptr(),
-        layout.block_m, layout.block_n, int(bool(causal)), float(softmax_scale), ws.data_ptr(),
-        ws_bytes, _stream_ptr(stream))
+    head = (Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), lse.data_ptr(),
+            dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), AP_BF16, B, H, Lq, Lk, D,
+            _strides3(Q), _strides3(K), _strides3(V), _strides3(O),
+            layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
+            layout_t.col_ptr.data_ptr(), layout_t.row_idx.data_ptr(), layout_t.tile_idx.data_ptr(),
+            layout.block_m, layout.block_n)
+    tail = (int(bool(causal)), float(softmax_scale), ws.data_ptr(), ws_bytes, _stream_ptr(stream))
+    if sched is None and col_sched is None:
+        st = lib().ap_sparse_attn_bwd(*head, *tail)
+    else:
+        cs = sched.c_struct() if sched is not None else None
+        ccs = col_sched.c_struct() if col_sched is not None else None
+        st = lib().ap_sparse_attn_bwd_sched(*head, ctypes.byref(cs) if cs is not None else None,
+                                            ctypes.byref(ccs) if ccs is not None else None, *tail)
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_bwd")
     return dQ, dK, dV

@@ -1,5 +1,6 @@
 // C ABI of the library: host-side validation and dispatch.  See include/ap.h for the contract.
 #include <hip/hip_runtime.h>
+#include <initializer_list>
 #include <math.h>
 #include <stdint.h>
 
@@ -244,7 +245,7 @@ size_t ap_bwd_workspace_bytes(int B, int H, int Lq)
     return (size_t)B * (size_t)H * (size_t)Lq * sizeof(float);
 }
 
-ap_status ap_sparse_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
+static ap_status bwd_common(const void* Q, const void* K, const void* V, const void* O,
                              const void* dO, const float* lse, void* dQ, void* dK, void* dV,
                              ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
                              const int64_t* stride_q, const int64_t* stride_k,
@@ -252,8 +253,8 @@ ap_status ap_sparse_attn_bwd(const void* Q, const void* K, const void* V, const 
                              const int32_t* row_ptr, const int32_t* col_idx,
                              const uint64_t* bitmaps, const int32_t* col_ptr,
                              const int32_t* row_idx, const int32_t* tile_idx, int block_m,
-                             int block_n, int causal, float softmax_scale, void* workspace,
-                             size_t workspace_bytes, void* stream)
+                             int block_n, const ap_schedule* sched, const ap_schedule* col_sched, int causal,
+                             float softmax_scale, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!Q || !K || !V || !O || !dO || !lse || !dQ || !dK || !dV || !stride_q || !stride_k ||
         !stride_v || !stride_o || !row_ptr || !col_idx || !bitmaps || !col_ptr || !row_idx ||
@@ -288,6 +289,12 @@ ap_status ap_sparse_attn_bwd(const void* Q, const void* K, const void* V, const 
     // bitmap rows are fetched with 32-bit byte offsets: 512 bytes per tile
     if (nQB * nKB * H >= (1LL << 22)) return AP_ERR_UNSUPPORTED;
     if (workspace_bytes < ap_bwd_workspace_bytes(B, H, Lq)) return AP_ERR_CAPACITY;
+    for (const ap_schedule* sc : {sched, col_sched}) {
+        if (!sc) continue;
+        if (!sc->cnt || !sc->start || !sc->cols || !sc->bitmaps) return AP_ERR_INVALID_ARG;
+        if (!aligned(sc->cnt, 4) || !aligned(sc->start, 4) || !aligned(sc->cols, 4) || !aligned(sc->bitmaps, 8))
+            return AP_ERR_INVALID_ARG;
+    }
 
     ap::BwdArgs a;
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.lse = lse;
@@ -301,7 +308,67 @@ ap_status ap_sparse_attn_bwd(const void* Q, const void* K, const void* V, const 
     a.causal = causal ? 1 : 0;
     a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
     a.delta = (float*)workspace;
+    a.sched = sched ? ap::Schedule{sched->cnt, sched->start, sched->cols, sched->bitmaps}
+                    : ap::Schedule{nullptr, nullptr, nullptr, nullptr};
+    a.csched = col_sched ? ap::Schedule{col_sched->cnt, col_sched->start, col_sched->cols, col_sched->bitmaps}
+                         : ap::Schedule{nullptr, nullptr, nullptr, nullptr};
     return ap::launch_bwd(a, (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+ap_status ap_sparse_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
+                             const void* dO, const float* lse, void* dQ, void* dK, void* dV,
+                             ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                             const int64_t* stride_q, const int64_t* stride_k,
+                             const int64_t* stride_v, const int64_t* stride_o,
+                             const int32_t* row_ptr, const int32_t* col_idx,
+                             const uint64_t* bitmaps, const int32_t* col_ptr,
+                             const int32_t* row_idx, const int32_t* tile_idx, int block_m,
+                             int block_n, int causal, float softmax_scale, void* workspace,
+                             size_t workspace_bytes, void* stream)
+{
+    return bwd_common(Q, K, V, O, dO, lse, dQ, dK, dV, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v,
+                      stride_o, row_ptr, col_idx, bitmaps, col_ptr, row_idx, tile_idx, block_m, block_n,
+                      nullptr, nullptr, causal, softmax_scale, workspace, workspace_bytes, stream);
+}
+
+ap_status ap_sparse_attn_bwd_sched(const void* Q, const void* K, const void* V, const void* O,
+                                   const void* dO, const float* lse, void* dQ, void* dK, void* dV,
+                                   ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                   const int64_t* stride_q, const int64_t* stride_k,
+                                   const int64_t* stride_v, const int64_t* stride_o,
+                                   const int32_t* row_ptr, const int32_t* col_idx,
+                                   const uint64_t* bitmaps, const int32_t* col_ptr,
+                                   const int32_t* row_idx, const int32_t* tile_idx, int block_m,
+                                   int block_n, const ap_schedule* sched,
+                                   const ap_schedule* col_sched, int causal, float softmax_scale,
+                                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    return bwd_common(Q, K, V, O, dO, lse, dQ, dK, dV, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v,
+                      stride_o, row_ptr, col_idx, bitmaps, col_ptr, row_idx, tile_idx, block_m, block_n,
+                      sched, col_sched, causal, softmax_scale, workspace, workspace_bytes, stream);
+}
+
+ap_status ap_build_col_schedule(const int32_t* col_ptr, const int32_t* row_idx, const int32_t* tile_idx,
+                                const uint64_t* bitmaps, int H, int Lq, int Lk, int block_m,
+                                int block_n, int64_t cap, int causal, int min_rows,
+                                const ap_schedule* col_sched, void* stream)
+{
+    if (!col_ptr || !row_idx || !tile_idx || !bitmaps || !col_sched) return AP_ERR_INVALID_ARG;
+    if (!col_sched->cnt || !col_sched->start || !col_sched->cols || !col_sched->bitmaps) return AP_ERR_INVALID_ARG;
+    if (H <= 0 || Lq <= 0 || Lk <= 0 || cap < 0) return AP_ERR_INVALID_ARG;
+    if (causal && Lk < Lq) return AP_ERR_INVALID_ARG;
+    if (min_rows < 0 || min_rows > 65) return AP_ERR_INVALID_ARG;
+    if (block_m != 64 || block_n != 64) return AP_ERR_UNSUPPORTED;
+    if (!ap::layout_shape_ok(H, Lq, Lk, block_m, block_n)) return AP_ERR_UNSUPPORTED;
+    if (!aligned(col_ptr, 4) || !aligned(row_idx, 4) || !aligned(tile_idx, 4) || !aligned(bitmaps, 8) ||
+        !aligned(col_sched->cnt, 4) || !aligned(col_sched->start, 4) || !aligned(col_sched->cols, 4) ||
+        !aligned(col_sched->bitmaps, 8))
+        return AP_ERR_INVALID_ARG;
+    ap::Schedule s{col_sched->cnt, col_sched->start, col_sched->cols, col_sched->bitmaps};
+    const hipError_t e = ap::launch_build_col_schedule(col_ptr, row_idx, tile_idx, bitmaps, H, Lq, Lk,
+                                                       causal ? 1 : 0, min_rows == 0 ? 48 : min_rows, s,
+                                                       (hipStream_t)stream);
+    return e == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
 size_t ap_attention_maps_workspace_bytes(int B, int H, int Lq)

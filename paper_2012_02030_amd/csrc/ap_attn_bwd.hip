@@ -387,9 +387,14 @@ hipError_t launch_d(const BwdArgs& a, hipStream_t stream)
     hipLaunchKernelGGL(bwd_delta_kernel<D>, dim3((unsigned)((dthreads + 255) / 256)), dim3(256), 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((unsigned)(a.B * a.H * nQP)), dim3(256), 0, stream, a, nQB, nQP);
-    e = hipGetLastError();
+    if (a.sched.cnt) {
+        e = launch_bwd_sched(a, true, false, stream);
+    } else {
+        hipLaunchKernelGGL(bwd_dq_kernel<D>, dim3((unsigned)(a.B * a.H * nQP)), dim3(256), 0, stream, a, nQB, nQP);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
+    if (a.csched.cnt) return launch_bwd_sched(a, false, true, stream);
     hipLaunchKernelGGL(bwd_dkv_kernel<D>, dim3((unsigned)(a.B * a.H * nKP)), dim3(256), 0, stream, a, nQB, nKB, nKP);
     return hipGetLastError();
 }

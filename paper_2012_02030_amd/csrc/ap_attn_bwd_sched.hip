@@ -1,0 +1,312 @@
+// Backward pass over visit schedules: the same arithmetic as ap_attn_bwd.hip, but dQ walks the
+// entries of the row schedule (runs of 64 consecutive keys or 64 gathered keys per block row) and
+// dK, dV walk the entries of the column schedule (runs of 64 consecutive queries or 64 gathered
+// queries per block column), so the backward pass skips what the forward pass skips.  Causal
+// limits are folded into the entry bitmaps by the schedule builders.
+//
+// One workgroup of two wavefronts per block row (dQ) or block column (dK, dV); one LDS stage: the
+// loads of an entry are issued, waited for and consumed in turn, several workgroups per compute
+// unit cover each other's waits.  The gather keys (or queries) of the next entry are fetched into
+// registers while the current entry is computed, so that its loads can be issued at once.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ap_internal.h"
+#include "ap_mfma_common.h"
+
+namespace ap {
+
+namespace {
+
+using namespace mfma;
+
+__device__ __forceinline__ float lse2_of(float lse) { return lse == -INFINITY ? INFINITY : lse * kLog2e; }
+
+template <int D>
+__global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB)
+{
+    constexpr int TILE = kBN * D;
+    constexpr int KSTEPS = D / 16;
+    constexpr int DBLK = D / 32;
+    constexpr int RPI = 64 / (D / 8);
+    constexpr int NLOAD = (D / 8) / 2;
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[3 * TILE];
+    lds_u16* Kk = (lds_u16*)smem;                            // K rows, key swizzle (rows x Q^T)
+    lds_u16* Kv = Kk + TILE;                                 // K rows, value swizzle (K^T x dS^T)
+    lds_u16* Vk = Kv + TILE;                                 // V rows, key swizzle (rows x dO^T)
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int n = lane & 31, hh = lane >> 5;
+    const int g_row = lane / (D / 8);
+
+    const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int qb = nQB - 1 - (bid % nQB);
+    const int h = (bid / nQB) % a.H;
+    const int b = bid / (nQB * a.H);
+
+    const uint16_t* Qp = (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1];
+    const uint16_t* Gp = (const uint16_t*)a.dO + (size_t)b * a.so[0] + (size_t)h * a.so[1];
+    const uint16_t* Kp = (const uint16_t*)a.K + (size_t)b * a.sk[0] + (size_t)h * a.sk[1];
+    const uint16_t* Vp = (const uint16_t*)a.V + (size_t)b * a.sv[0] + (size_t)h * a.sv[1];
+    uint16_t* dQp = (uint16_t*)a.dQ + (size_t)b * a.sq[0] + (size_t)h * a.sq[1];
+    const int sk_bytes = (int)a.sk[2] * 2, sv_bytes = (int)a.sv[2] * 2;
+    const rsrc_t k_rsrc = make_rsrc(Kp, (unsigned)((a.Lk - 1) * sk_bytes + D * 2));
+    const rsrc_t v_rsrc = make_rsrc(Vp, (unsigned)((a.Lk - 1) * sv_bytes + D * 2));
+
+    const int brow = wave * 32 + n;
+    const int qrow = qb * 64 + brow;
+    const bool row_ok = qrow < a.Lq;
+    const int qload = row_ok ? qrow : a.Lq - 1;
+    bf16x8 qreg[KSTEPS], greg[KSTEPS];                       // Q^T and dO^T operands
+    {
+        const uint16_t* qr = Qp + (size_t)qload * a.sq[2] + 8 * hh;
+        const uint16_t* gr = Gp + (size_t)qload * a.so[2] + 8 * hh;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            qreg[kk] = *reinterpret_cast<const bf16x8*>(qr + 16 * kk);
+            greg[kk] = *reinterpret_cast<const bf16x8*>(gr + 16 * kk);
+        }
+    }
+    const size_t stat = ((size_t)b * a.H + h) * a.Lq + qload;
+    const float lse2 = row_ok ? lse2_of(a.lse[stat]) : INFINITY;
+    const float delta = row_ok ? a.delta[stat] : 0.f;
+    const float sc = a.scale * kLog2e;
+    const int k_swz = hh ^ swz_k<D>(n);
+    const TrRead tr = make_tr_read<D>(lane);
+
+    f32x16 dqacc[DBLK];
+#pragma unroll
+    for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dqacc[db][i] = 0.f;
+
+    const int r = h * nQB + qb;
+    const int t0 = a.row_ptr[r];
+    const int t1 = t0 + a.sched.cnt[r];
+    auto load_keys = [&](int t, int* gk) {                   // gather keys of the rows this lane loads
+#pragma unroll
+        for (int u = 0; u < NLOAD; ++u) gk[u] = a.sched.cols[(size_t)t * 64 + (wave + 2 * u) * RPI + g_row];
+    };
+    int s_cur = t0 < t1 ? a.sched.start[t0] : 0;
+    int gcur[NLOAD], gnext[NLOAD];
+#pragma unroll
+    for (int u = 0; u < NLOAD; ++u) gcur[u] = gnext[u] = 0;
+    if (t0 < t1 && s_cur < 0) load_keys(t0, gcur);
+
+    for (int t = t0; t < t1; ++t) {
+        __syncthreads();                                     // the previous entry is consumed
+        if (s_cur >= 0) {
+            issue_tile_loads<D, 2, false>(k_rsrc, Kk, s_cur, sk_bytes, wave, lane);
+            issue_tile_loads<D, 2, true>(k_rsrc, Kv, s_cur, sk_bytes, wave, lane);
+            issue_tile_loads<D, 2, false>(v_rsrc, Vk, s_cur, sv_bytes, wave, lane);
+        } else {
+            issue_gather_loads<D, 2, false>(k_rsrc, Kk, gcur, sk_bytes, wave, lane);
+            issue_gather_loads<D, 2, true>(k_rsrc, Kv, gcur, sk_bytes, wave, lane);
+            issue_gather_loads<D, 2, false>(v_rsrc, Vk, gcur, sv_bytes, wave, lane);
+        }
+        const uint64_t word = a.sched.bitmaps[(size_t)t * 64 + brow];   // causal limit folded in
+        int s_nxt = 0;
+        if (t + 1 < t1) {
+            s_nxt = a.sched.start[t + 1];
+            if (s_nxt < 0) load_keys(t + 1, gnext);
+        }
+        wait_vmem();
+        __syncthreads();
+        if (__ballot(word != 0) != 0) {
+            f32x16 sacc[2], pacc[2];
+            qk_64<D>(smem, qreg, n, k_swz, sacc);            // S^T  = K Q^T
+            qk_64<D>(smem + 2 * TILE, greg, n, k_swz, pacc); // dP^T = V dO^T
+            const uint64_t wsh = word >> (4 * hh);
+            const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int pos = 8 * (i / 4) + (i % 4);
+                    const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)wbits[kb], pos, 1);
+                    const float x = fmaf(sacc[kb][i], sc, -lse2);
+                    const float p = __builtin_amdgcn_exp2f(__uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep)));
+                    sacc[kb][i] = p * (pacc[kb][i] - delta); // dS^T
+                }
+            tr_mm_64<D>(Kv, sacc, dqacc, tr);                // dQ^T += K^T dS^T
+        }
+        s_cur = s_nxt;
+#pragma unroll
+        for (int u = 0; u < NLOAD; ++u) gcur[u] = gnext[u];
+    }
+    __syncthreads();                                         // all wavefronts are done with the tiles
+    store_rows_bf16<D>(smem + wave * 32 * D, dqacc, a.scale, lane,
+                       dQp + (size_t)(qb * 64 + wave * 32) * a.sq[2], a.sq[2], a.Lq - (qb * 64 + wave * 32));
+}
+
+template <int D>
+__global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nKB)
+{
+    constexpr int TILE = kBN * D;
+    constexpr int KSTEPS = D / 16;
+    constexpr int DBLK = D / 32;
+    constexpr int RPI = 64 / (D / 8);
+    constexpr int NLOAD = (D / 8) / 2;
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[4 * TILE];
+    __shared__ __attribute__((aligned(16))) float s_lse2[64];
+    __shared__ __attribute__((aligned(16))) float s_delta[64];
+    __shared__ __attribute__((aligned(16))) uint64_t s_word[64];
+    lds_u16* Qk = (lds_u16*)smem;                            // Q rows, key swizzle   (rows x K^T)
+    lds_u16* Qv = Qk + TILE;                                 // Q rows, value swizzle (Q^T x dS)
+    lds_u16* Gk = Qv + TILE;                                 // dO rows, key swizzle  (rows x V^T)
+    lds_u16* Gv = Gk + TILE;                                 // dO rows, value swizzle (dO^T x P)
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int n = lane & 31, hh = lane >> 5;
+    const int g_row = lane / (D / 8);
+
+    const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int kb = bid % nKB;
+    const int h = (bid / nKB) % a.H;
+    const int b = bid / (nKB * a.H);
+
+    const uint16_t* Qp = (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1];
+    const uint16_t* Gp = (const uint16_t*)a.dO + (size_t)b * a.so[0] + (size_t)h * a.so[1];
+    const uint16_t* Kp = (const uint16_t*)a.K + (size_t)b * a.sk[0] + (size_t)h * a.sk[1];
+    const uint16_t* Vp = (const uint16_t*)a.V + (size_t)b * a.sv[0] + (size_t)h * a.sv[1];
+    uint16_t* dKp = (uint16_t*)a.dK + (size_t)b * a.sk[0] + (size_t)h * a.sk[1];
+    uint16_t* dVp = (uint16_t*)a.dV + (size_t)b * a.sv[0] + (size_t)h * a.sv[1];
+    const int sq_bytes = (int)a.sq[2] * 2, so_bytes = (int)a.so[2] * 2;
+    const rsrc_t q_rsrc = make_rsrc(Qp, (unsigned)((a.Lq - 1) * sq_bytes + D * 2));
+    const rsrc_t g_rsrc = make_rsrc(Gp, (unsigned)((a.Lq - 1) * so_bytes + D * 2));
+    const size_t stat_base = ((size_t)b * a.H + h) * a.Lq;
+
+    const int key = kb * 64 + wave * 32 + n;
+    const int kload = key < a.Lk ? key : a.Lk - 1;
+    bf16x8 kreg[KSTEPS], vreg[KSTEPS];                       // K^T and V^T operands
+    {
+        const uint16_t* kr = Kp + (size_t)kload * a.sk[2] + 8 * hh;
+        const uint16_t* vr = Vp + (size_t)kload * a.sv[2] + 8 * hh;
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            kreg[kk] = *reinterpret_cast<const bf16x8*>(kr + 16 * kk);
+            vreg[kk] = *reinterpret_cast<const bf16x8*>(vr + 16 * kk);
+        }
+    }
+    const float sc = a.scale * kLog2e;
+    const int k_swz = hh ^ swz_k<D>(n);
+    const TrRead tr = make_tr_read<D>(lane);
+    const int kcol = wave * 32 + n;                          // this lane's key inside the block column
+
+    f32x16 dkacc[DBLK], dvacc[DBLK];
+#pragma unroll
+    for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            dkacc[db][i] = 0.f;
+            dvacc[db][i] = 0.f;
+        }
+
+    const int c = h * nKB + kb;
+    const int t0 = a.col_ptr[c];
+    const int t1 = t0 + a.csched.cnt[c];
+    auto load_rows = [&](int t, int* gq, int& mine) {        // gathered queries: of the rows this lane
+        // loads, and (first 64 threads) of the slot whose statistics this thread fetches
+#pragma unroll
+        for (int u = 0; u < NLOAD; ++u) gq[u] = a.csched.cols[(size_t)t * 64 + (wave + 2 * u) * RPI + g_row];
+        if (tid < 64) mine = a.csched.cols[(size_t)t * 64 + tid];
+    };
+    int s_cur = t0 < t1 ? a.csched.start[t0] : 0;
+    int gcur[NLOAD], gnext[NLOAD], qmine = 0, qmine_next = 0;
+#pragma unroll
+    for (int u = 0; u < NLOAD; ++u) gcur[u] = gnext[u] = 0;
+    if (t0 < t1 && s_cur < 0) load_rows(t0, gcur, qmine);
+
+    for (int t = t0; t < t1; ++t) {
+        __syncthreads();                                     // the previous entry is consumed
+        if (s_cur >= 0) {
+            issue_tile_loads<D, 2, false>(q_rsrc, Qk, s_cur, sq_bytes, wave, lane);
+            issue_tile_loads<D, 2, true>(q_rsrc, Qv, s_cur, sq_bytes, wave, lane);
+            issue_tile_loads<D, 2, false>(g_rsrc, Gk, s_cur, so_bytes, wave, lane);
+            issue_tile_loads<D, 2, true>(g_rsrc, Gv, s_cur, so_bytes, wave, lane);
+        } else {
+            issue_gather_loads<D, 2, false>(q_rsrc, Qk, gcur, sq_bytes, wave, lane);
+            issue_gather_loads<D, 2, true>(q_rsrc, Qv, gcur, sq_bytes, wave, lane);
+            issue_gather_loads<D, 2, false>(g_rsrc, Gk, gcur, so_bytes, wave, lane);
+            issue_gather_loads<D, 2, true>(g_rsrc, Gv, gcur, so_bytes, wave, lane);
+        }
+        if (tid < 64) {                                      // per-query statistics and bitmap words
+            const int q = s_cur >= 0 ? s_cur + tid : qmine;
+            const bool ok = q < a.Lq;
+            s_lse2[tid] = ok ? lse2_of(a.lse[stat_base + q]) : INFINITY;
+            s_delta[tid] = ok ? a.delta[stat_base + q] : 0.f;
+            s_word[tid] = a.csched.bitmaps[(size_t)t * 64 + tid];
+        }
+        int s_nxt = 0;
+        if (t + 1 < t1) {
+            s_nxt = a.csched.start[t + 1];
+            if (s_nxt < 0) load_rows(t + 1, gnext, qmine_next);
+        }
+        wait_vmem();
+        __syncthreads();
+        f32x16 sacc[2], pacc[2];
+        qk_64<D>(smem, kreg, n, k_swz, sacc);                // S  = Q K^T   (rows: queries, lane: key)
+        qk_64<D>(smem + 2 * TILE, vreg, n, k_swz, pacc);     // dP = dO V^T
+#pragma unroll
+        for (int qblk = 0; qblk < 2; ++qblk)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int r0 = 32 * qblk + 8 * g + 4 * hh;   // 4 consecutive query slots
+                const float4 l4 = *reinterpret_cast<const float4*>(&s_lse2[r0]);
+                const float4 d4 = *reinterpret_cast<const float4*>(&s_delta[r0]);
+                const float le[4] = {l4.x, l4.y, l4.z, l4.w}, de[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = 4 * g + e;
+                    const bool kept = (s_word[r0 + e] >> kcol) & 1ull;
+                    const float p = kept ? __builtin_amdgcn_exp2f(fmaf(sacc[qblk][i], sc, -le[e])) : 0.f;
+                    sacc[qblk][i] = p;                       // P
+                    pacc[qblk][i] = p * (pacc[qblk][i] - de[e]);   // dS
+                }
+            }
+        tr_mm_64<D>(Gv, sacc, dvacc, tr);                    // dV^T += dO^T P
+        tr_mm_64<D>(Qv, pacc, dkacc, tr);                    // dK^T += Q^T dS
+        s_cur = s_nxt;
+        qmine = qmine_next;
+#pragma unroll
+        for (int u = 0; u < NLOAD; ++u) gcur[u] = gnext[u];
+    }
+    __syncthreads();                                         // all wavefronts are done with the tiles
+    const int krow0 = kb * 64 + wave * 32;
+    uint16_t* stage = smem + wave * 32 * D;
+    store_rows_bf16<D>(stage, dkacc, a.scale, lane, dKp + (size_t)krow0 * a.sk[2], a.sk[2], a.Lk - krow0);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the staging area is reused
+    store_rows_bf16<D>(stage, dvacc, 1.0f, lane, dVp + (size_t)krow0 * a.sv[2], a.sv[2], a.Lk - krow0);
+}
+
+template <int D>
+hipError_t launch_d(const BwdArgs& a, bool dq, bool dkv, hipStream_t stream)
+{
+    const int nQB = (a.Lq + 63) / 64, nKB = (a.Lk + 63) / 64;
+    if (dq) {
+        hipLaunchKernelGGL(bwd_dq_sched_kernel<D>, dim3((unsigned)(a.B * a.H * nQB)), dim3(128), 0, stream, a, nQB);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (dkv)
+        hipLaunchKernelGGL(bwd_dkv_sched_kernel<D>, dim3((unsigned)(a.B * a.H * nKB)), dim3(128), 0, stream, a, nKB);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_bwd_sched(const BwdArgs& a, bool dq, bool dkv, hipStream_t stream)
+{
+    switch (a.D) {
+        case 32: return launch_d<32>(a, dq, dkv, stream);
+        case 64: return launch_d<64>(a, dq, dkv, stream);
+        case 128: return launch_d<128>(a, dq, dkv, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace ap

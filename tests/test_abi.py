@@ -260,6 +260,52 @@ def test_backward_arguments(L):
     assert tr(fake, fake + 2, 2, 64, 64, 64, 64, 8, fake, fake, fake, None) == ap.AP_ERR_INVALID_ARG
 
 
+def test_scheduled_backward_arguments(L):
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+    ws = ap.ap_bwd_workspace_bytes(1, 2, 64)
+    good = ap._CSchedule(fake, fake, fake, fake)
+    hole = ap._CSchedule(fake, None, fake, fake)
+    odd = ap._CSchedule(fake, fake, fake, fake + 4)                            # bitmaps not 8-byte aligned
+
+    def bwd(sched, col_sched, **over):
+        a = dict(dtype=ap.AP_BF16, bm=64, causal=0, Lq=64, Lk=64)
+        a.update(over)
+        ptrs = [fake + i * 0x100000 for i in range(9)]
+        return L.ap_sparse_attn_bwd_sched(*ptrs, a["dtype"], 1, 2, a["Lq"], a["Lk"], 64, s, s, s, s, fake, fake,
+                                          fake, fake, fake, fake, a["bm"], 64,
+                                          ctypes.byref(sched) if sched else None,
+                                          ctypes.byref(col_sched) if col_sched else None, a["causal"], 0.0,
+                                          fake, ws, None)
+
+    assert bwd(hole, None) == ap.AP_ERR_INVALID_ARG
+    assert bwd(None, hole) == ap.AP_ERR_INVALID_ARG
+    assert bwd(good, odd) == ap.AP_ERR_INVALID_ARG
+    assert bwd(good, good, dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    assert bwd(good, good, bm=128) == ap.AP_ERR_UNSUPPORTED
+    assert bwd(good, good, causal=1, Lq=128) == ap.AP_ERR_INVALID_ARG
+
+    def build(**over):
+        a = dict(col_ptr=fake, row_idx=fake, tile_idx=fake, bitmaps=fake, H=2, Lq=64, Lk=64, bm=64, bn=64,
+                 cap=8, causal=0, min_rows=0, sched=good)
+        a.update(over)
+        return L.ap_build_col_schedule(a["col_ptr"], a["row_idx"], a["tile_idx"], a["bitmaps"], a["H"], a["Lq"],
+                                       a["Lk"], a["bm"], a["bn"], a["cap"], a["causal"], a["min_rows"],
+                                       ctypes.byref(a["sched"]) if a["sched"] else None, None)
+
+    assert build(col_ptr=None) == ap.AP_ERR_INVALID_ARG
+    assert build(sched=None) == ap.AP_ERR_INVALID_ARG
+    assert build(sched=hole) == ap.AP_ERR_INVALID_ARG
+    assert build(sched=odd) == ap.AP_ERR_INVALID_ARG
+    assert build(H=0) == ap.AP_ERR_INVALID_ARG
+    assert build(cap=-1) == ap.AP_ERR_INVALID_ARG
+    assert build(min_rows=66) == ap.AP_ERR_INVALID_ARG
+    assert build(min_rows=-1) == ap.AP_ERR_INVALID_ARG
+    assert build(causal=1, Lq=128) == ap.AP_ERR_INVALID_ARG
+    assert build(bm=128) == ap.AP_ERR_UNSUPPORTED
+    assert build(tile_idx=fake + 2) == ap.AP_ERR_INVALID_ARG
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ap, "_lib", None)
     monkeypatch.setattr(ap, "LIB_PATH", "/nonexistent/libap_mi355x.so")

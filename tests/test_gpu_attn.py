@@ -166,6 +166,35 @@ def test_strided_inputs():
         assert np.abs(lse.to(torch.float64).cpu().numpy() - lse_ref).max() <= TOL[dtype]
 
 
+def nan_padded(t, extra=64):
+    """The same values as t [B, H, L, D], stored with `extra` rows of NaN behind every head's last row."""
+    B, H, L, D = t.shape
+    store = torch.full((B, H, L + extra, D), float("nan"), dtype=t.dtype, device=t.device)
+    store[:, :, :L] = t
+    return store[:, :, :L]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rows_behind_the_last_key_are_never_used(dtype):
+    # a ragged last key tile must not pick up what is stored behind row Lk - 1 of a head
+    H, Lq, Lk, D = 2, 130, 150, 128
+    Q, K, V = qkv(31, 2, H, Lq, Lk, D)
+    mask = synth.random_mask(H, Lq, Lk, 0.4, 32)
+    mask[:, :, Lk - 1] = 1
+    dq, rq = to_device(Q, dtype)
+    dk, rk = to_device(K, dtype)
+    dv, rv = to_device(V, dtype)
+    lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
+    O_ref, lse_ref = oracle.masked_attention(rq, rk, rv, mask, causal=False)
+    for sched in (None, ap.ap_build_schedule(lay, causal=False)) if dtype == "bf16" else (None,):
+        O, lse = ap.ap_sparse_attn_fwd(dq, nan_padded(dk), nan_padded(dv), lay, sched=sched)
+        torch.cuda.synchronize()
+        O_h = O.to(torch.float64).cpu().numpy()
+        assert np.all(np.isfinite(O_h))
+        assert np.abs(O_h - O_ref).max() <= TOL[dtype]
+        assert np.abs(lse.to(torch.float64).cpu().numpy() - lse_ref).max() <= TOL[dtype]
+
+
 def test_output_is_bitwise_reproducible():
     cfg = synth.CONFIGS["C3"]
     Q, K, V = synth.make_qkv(cfg)
