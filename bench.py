@@ -411,7 +411,7 @@ def main():
                                                        sched=rs, col_sched=cs), steps)
         cs_ms = timed(lambda: ap.ap_build_col_schedule(lay, lt, causal=cfg.causal), steps)
         row_entries = int(rs.cnt.sum().item())
-        col_entries = int(cs.cnt.sum().item())
+        col_entries = int(cs.cnt[:lt.col_ptr.shape[0] - 1].sum().item())
         kept = int(mask_np.sum())
         kept_flop = 10.0 * cfg.D * kept * cfg.B               # five N^2-sized products per kept entry
         tiles = int(lay.nnz.item())

@@ -293,7 +293,10 @@ ap_status ap_sparse_attn_bwd(const void *Q, const void *K, const void *V, const 
  * per block row).  dK and dV walk a column schedule, the same structure with rows and columns
  * swapped, built from the transposed layout by ap_build_col_schedule: entry e of block column c
  * is element col_ptr[c] + e of its arrays;
- *     cnt   [H * ceil(Lk/64)]  entries of each block column
+ *     cnt   [2 * H * nKB + H], nKB = ceil(Lk/64): the entries of each block column [H * nKB],
+ *                              then the visiting order of each head's block columns [H * nKB]
+ *                              (columns with at least twice the head's mean number of entries
+ *                              first), then the number of such columns per head [H]
  *     start [cap]              >= 0: first query of 64 consecutive queries; -1: gathered queries
  *     cols  [cap*64]           query index per slot of a gathered entry; empty slots hold Lq
  *     bitmaps [cap*64]         per query slot: bit c set = key 64*kb + c kept and visible

@@ -382,7 +382,7 @@ def ap_build_col_schedule(layout: Layout, layout_t: LayoutT, causal: bool = Fals
     dev = layout.row_ptr.device
     cap = int(layout.col_idx.shape[0])
     ncols = int(layout_t.col_ptr.shape[0]) - 1
-    sched = Schedule(torch.empty(ncols, dtype=torch.int32, device=dev),
+    sched = Schedule(torch.empty(2 * ncols + layout.H, dtype=torch.int32, device=dev),
                      torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
                      torch.empty((max(cap, 1), 64), dtype=torch.int32, device=dev),
                      torch.empty((max(cap, 1), 64), dtype=torch.int64, device=dev),

@@ -4,10 +4,11 @@
 // queries per block column), so the backward pass skips what the forward pass skips.  Causal
 // limits are folded into the entry bitmaps by the schedule builders.
 //
-// One workgroup of two wavefronts per block row (dQ) or block column (dK, dV); one LDS stage: the
-// loads of an entry are issued, waited for and consumed in turn, several workgroups per compute
-// unit cover each other's waits.  The gather keys (or queries) of the next entry are fetched into
-// registers while the current entry is computed, so that its loads can be issued at once.
+// One workgroup of two wavefronts per block row (dQ) or block column (dK, dV).  Every tile is
+// stored once in LDS, with a swizzle that suits both the row-wise reads (scores) and the
+// transposing reads (gradient products).  Two LDS stages: the next entry's tiles travel while the
+// current entry is computed; the metadata of the entry after that (start, gather indices, bitmap
+// words, per-query statistics) is fetched into registers in the same step.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -30,10 +31,9 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB
     constexpr int DBLK = D / 32;
     constexpr int RPI = 64 / (D / 8);
     constexpr int NLOAD = (D / 8) / 2;
-    __shared__ __attribute__((aligned(1024))) uint16_t smem[3 * TILE];
-    lds_u16* Kk = (lds_u16*)smem;                            // K rows, key swizzle (rows x Q^T)
-    lds_u16* Kv = Kk + TILE;                                 // K rows, value swizzle (K^T x dS^T)
-    lds_u16* Vk = Kv + TILE;                                 // V rows, key swizzle (rows x dO^T)
+    constexpr int STAGE = 2 * TILE;                          // K rows, V rows
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * STAGE];
+    lds_u16* lds = (lds_u16*)smem;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -70,11 +70,11 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB
         }
     }
     const size_t stat = ((size_t)b * a.H + h) * a.Lq + qload;
-    const float lse2 = row_ok ? lse2_of(a.lse[stat]) : INFINITY;
-    const float delta = row_ok ? a.delta[stat] : 0.f;
+    float lse2 = row_ok ? lse2_of(a.lse[stat]) : INFINITY;
+    float delta = row_ok ? a.delta[stat] : 0.f;
     const float sc = a.scale * kLog2e;
-    const int k_swz = hh ^ swz_k<D>(n);
-    const TrRead tr = make_tr_read<D>(lane);
+    const int k_swz = hh ^ swz_u<D>(n);
+    const TrReadU<D> tr = make_tr_read_u<D>(lane);
 
     f32x16 dqacc[DBLK];
 #pragma unroll
@@ -85,39 +85,59 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB
     const int r = h * nQB + qb;
     const int t0 = a.row_ptr[r];
     const int t1 = t0 + a.sched.cnt[r];
-    auto load_keys = [&](int t, int* gk) {                   // gather keys of the rows this lane loads
-#pragma unroll
-        for (int u = 0; u < NLOAD; ++u) gk[u] = a.sched.cols[(size_t)t * 64 + (wave + 2 * u) * RPI + g_row];
-    };
-    int s_cur = t0 < t1 ? a.sched.start[t0] : 0;
-    int gcur[NLOAD], gnext[NLOAD];
-#pragma unroll
-    for (int u = 0; u < NLOAD; ++u) gcur[u] = gnext[u] = 0;
-    if (t0 < t1 && s_cur < 0) load_keys(t0, gcur);
 
-    for (int t = t0; t < t1; ++t) {
-        __syncthreads();                                     // the previous entry is consumed
-        if (s_cur >= 0) {
-            issue_tile_loads<D, 2, false>(k_rsrc, Kk, s_cur, sk_bytes, wave, lane);
-            issue_tile_loads<D, 2, true>(k_rsrc, Kv, s_cur, sk_bytes, wave, lane);
-            issue_tile_loads<D, 2, false>(v_rsrc, Vk, s_cur, sv_bytes, wave, lane);
+    // metadata of an entry: where it starts (or -1), the gather keys of the rows this lane loads
+    // (read for every entry, used by gathered ones only) and this lane's bitmap word
+    struct Meta {
+        int start;
+        int gk[NLOAD];
+        uint64_t word;
+    };
+    auto fetch = [&](int t, Meta& m) {
+        m.start = a.sched.start[t];
+#pragma unroll
+        for (int u = 0; u < NLOAD; ++u) m.gk[u] = a.sched.cols[(size_t)t * 64 + (wave + 2 * u) * RPI + g_row];
+        m.word = a.sched.bitmaps[(size_t)t * 64 + brow];     // causal limit folded in
+    };
+    auto issue = [&](const Meta& m, int stage) {
+        lds_u16* base = lds + stage * STAGE;
+        if (m.start >= 0) {
+            issue_tile_loads<D, 2, SWZ_BOTH>(k_rsrc, base, m.start, sk_bytes, wave, lane);
+            issue_tile_loads<D, 2, SWZ_BOTH>(v_rsrc, base + TILE, m.start, sv_bytes, wave, lane);
         } else {
-            issue_gather_loads<D, 2, false>(k_rsrc, Kk, gcur, sk_bytes, wave, lane);
-            issue_gather_loads<D, 2, true>(k_rsrc, Kv, gcur, sk_bytes, wave, lane);
-            issue_gather_loads<D, 2, false>(v_rsrc, Vk, gcur, sv_bytes, wave, lane);
+            issue_gather_loads<D, 2, SWZ_BOTH>(k_rsrc, base, m.gk, sk_bytes, wave, lane);
+            issue_gather_loads<D, 2, SWZ_BOTH>(v_rsrc, base + TILE, m.gk, sv_bytes, wave, lane);
         }
-        const uint64_t word = a.sched.bitmaps[(size_t)t * 64 + brow];   // causal limit folded in
-        int s_nxt = 0;
+    };
+
+    Meta cur, nxt;
+    if (t0 < t1) {
+        fetch(t0, cur);
+        issue(cur, 0);
+        nxt = cur;
+        if (t0 + 1 < t1) fetch(t0 + 1, nxt);
+    }
+    // first use of the loaded registers before the loop, so that no wait for them lands inside it
+    wait_vmem();
+    settle<KSTEPS>(qreg);
+    settle<KSTEPS>(greg);
+    asm volatile("" : "+v"(lse2), "+v"(delta));
+
+    int stage = 0;
+    for (int t = t0; t < t1; ++t) {
+        wait_vmem();                                         // entry t and the metadata of t + 1 have landed
+        __syncthreads();                                     // ... for everybody; the other stage is free
+        const uint64_t word = cur.word;
         if (t + 1 < t1) {
-            s_nxt = a.sched.start[t + 1];
-            if (s_nxt < 0) load_keys(t + 1, gnext);
+            issue(nxt, stage ^ 1);
+            cur = nxt;
+            if (t + 2 < t1) fetch(t + 2, nxt);
         }
-        wait_vmem();
-        __syncthreads();
         if (__ballot(word != 0) != 0) {
+            uint16_t* base = smem + stage * STAGE;
             f32x16 sacc[2], pacc[2];
-            qk_64<D>(smem, qreg, n, k_swz, sacc);            // S^T  = K Q^T
-            qk_64<D>(smem + 2 * TILE, greg, n, k_swz, pacc); // dP^T = V dO^T
+            qk_64<D>(base, qreg, n, k_swz, sacc);            // S^T  = K Q^T
+            qk_64<D>(base + TILE, greg, n, k_swz, pacc);     // dP^T = V dO^T
             const uint64_t wsh = word >> (4 * hh);
             const uint32_t wbits[2] = {(uint32_t)wsh, (uint32_t)(wsh >> 32)};
 #pragma unroll
@@ -130,11 +150,9 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB
                     const float p = __builtin_amdgcn_exp2f(__uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep)));
                     sacc[kb][i] = p * (pacc[kb][i] - delta); // dS^T
                 }
-            tr_mm_64<D>(Kv, sacc, dqacc, tr);                // dQ^T += K^T dS^T
+            tr_mm_64_u<D>(lds + stage * STAGE, sacc, dqacc, tr);   // dQ^T += K^T dS^T
         }
-        s_cur = s_nxt;
-#pragma unroll
-        for (int u = 0; u < NLOAD; ++u) gcur[u] = gnext[u];
+        stage ^= 1;
     }
     __syncthreads();                                         // all wavefronts are done with the tiles
     store_rows_bf16<D>(smem + wave * 32 * D, dqacc, a.scale, lane,
@@ -149,14 +167,12 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     constexpr int DBLK = D / 32;
     constexpr int RPI = 64 / (D / 8);
     constexpr int NLOAD = (D / 8) / 2;
-    __shared__ __attribute__((aligned(1024))) uint16_t smem[4 * TILE];
-    __shared__ __attribute__((aligned(16))) float s_lse2[64];
-    __shared__ __attribute__((aligned(16))) float s_delta[64];
-    __shared__ __attribute__((aligned(16))) uint64_t s_word[64];
-    lds_u16* Qk = (lds_u16*)smem;                            // Q rows, key swizzle   (rows x K^T)
-    lds_u16* Qv = Qk + TILE;                                 // Q rows, value swizzle (Q^T x dS)
-    lds_u16* Gk = Qv + TILE;                                 // dO rows, key swizzle  (rows x V^T)
-    lds_u16* Gv = Gk + TILE;                                 // dO rows, value swizzle (dO^T x P)
+    constexpr int STAGE = 2 * TILE;                          // Q rows, dO rows
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * STAGE];
+    __shared__ __attribute__((aligned(16))) float s_lse2[2][64];
+    __shared__ __attribute__((aligned(16))) float s_delta[2][64];
+    __shared__ __attribute__((aligned(16))) uint64_t s_word[2][64];
+    lds_u16* lds = (lds_u16*)smem;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -164,10 +180,43 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     const int n = lane & 31, hh = lane >> 5;
     const int g_row = lane / (D / 8);
 
-    const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int kb = bid % nKB;
-    const int h = (bid / nKB) % a.H;
-    const int b = bid / (nKB * a.H);
+    // Which (example, head) pair and which position of the head's visiting order this workgroup
+    // takes.  Every XCD gets a contiguous range of pairs (they share Q and dO rows in its L2); when
+    // the pairs divide evenly over the 8 XCDs, the heavy columns of all pairs of the range come
+    // first, so that the longest workgroups start at once, then the other columns pair by pair.
+    const int32_t* order = a.csched.cnt + (size_t)a.H * nKB;
+    const int32_t* n_heavy = order + (size_t)a.H * nKB;
+    const int NP = a.B * a.H;
+    int pair, idx;
+    if (NP % 8 == 0 && NP / 8 <= 64) {
+        const int PP = NP / 8, P0 = (blockIdx.x & 7) * PP;
+        int l = blockIdx.x >> 3;
+        pair = -1;
+        idx = 0;
+        for (int p = 0; p < PP && pair < 0; ++p) {
+            const int hv = n_heavy[(P0 + p) % a.H];
+            if (l < hv) {
+                pair = P0 + p;
+                idx = l;
+            }
+            l -= hv;
+        }
+        for (int p = 0; p < PP && pair < 0; ++p) {
+            const int hv = n_heavy[(P0 + p) % a.H];
+            if (l < nKB - hv) {
+                pair = P0 + p;
+                idx = hv + l;
+            }
+            l -= nKB - hv;
+        }
+    } else {
+        const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
+        pair = bid / nKB;
+        idx = bid % nKB;
+    }
+    const int h = pair % a.H;
+    const int b = pair / a.H;
+    const int kb = order[(size_t)h * nKB + idx];
 
     const uint16_t* Qp = (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1];
     const uint16_t* Gp = (const uint16_t*)a.dO + (size_t)b * a.so[0] + (size_t)h * a.so[1];
@@ -193,8 +242,8 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
         }
     }
     const float sc = a.scale * kLog2e;
-    const int k_swz = hh ^ swz_k<D>(n);
-    const TrRead tr = make_tr_read<D>(lane);
+    const int k_swz = hh ^ swz_u<D>(n);
+    const TrReadU<D> tr = make_tr_read_u<D>(lane);
     const int kcol = wave * 32 + n;                          // this lane's key inside the block column
 
     f32x16 dkacc[DBLK], dvacc[DBLK];
@@ -209,78 +258,108 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     const int c = h * nKB + kb;
     const int t0 = a.col_ptr[c];
     const int t1 = t0 + a.csched.cnt[c];
-    auto load_rows = [&](int t, int* gq, int& mine) {        // gathered queries: of the rows this lane
-        // loads, and (first 64 threads) of the slot whose statistics this thread fetches
-#pragma unroll
-        for (int u = 0; u < NLOAD; ++u) gq[u] = a.csched.cols[(size_t)t * 64 + (wave + 2 * u) * RPI + g_row];
-        if (tid < 64) mine = a.csched.cols[(size_t)t * 64 + tid];
-    };
-    int s_cur = t0 < t1 ? a.csched.start[t0] : 0;
-    int gcur[NLOAD], gnext[NLOAD], qmine = 0, qmine_next = 0;
-#pragma unroll
-    for (int u = 0; u < NLOAD; ++u) gcur[u] = gnext[u] = 0;
-    if (t0 < t1 && s_cur < 0) load_rows(t0, gcur, qmine);
 
-    for (int t = t0; t < t1; ++t) {
-        __syncthreads();                                     // the previous entry is consumed
-        if (s_cur >= 0) {
-            issue_tile_loads<D, 2, false>(q_rsrc, Qk, s_cur, sq_bytes, wave, lane);
-            issue_tile_loads<D, 2, true>(q_rsrc, Qv, s_cur, sq_bytes, wave, lane);
-            issue_tile_loads<D, 2, false>(g_rsrc, Gk, s_cur, so_bytes, wave, lane);
-            issue_tile_loads<D, 2, true>(g_rsrc, Gv, s_cur, so_bytes, wave, lane);
+    // metadata of an entry: where it starts (or -1), the gathered queries of the rows this lane
+    // loads and of the slot whose statistics this thread fetches (read for every entry, used by
+    // gathered ones only)
+    struct Meta {
+        int start;
+        int gq[NLOAD];
+        int mine;
+    };
+    // per-slot statistics of an entry, fetched by the first 64 threads one step ahead
+    struct Stat {
+        float lse, delta;
+        uint64_t word;
+    };
+    auto fetch = [&](int t, Meta& m) {
+        m.start = a.csched.start[t];
+#pragma unroll
+        for (int u = 0; u < NLOAD; ++u) m.gq[u] = a.csched.cols[(size_t)t * 64 + (wave + 2 * u) * RPI + g_row];
+        m.mine = tid < 64 ? a.csched.cols[(size_t)t * 64 + tid] : 0;
+    };
+    auto fetch_stat = [&](int t, const Meta& m, Stat& s) {
+        if (tid < 64) {
+            const int q = m.start >= 0 ? m.start + tid : m.mine;
+            const int ql = q < a.Lq ? q : a.Lq - 1;
+            const float l = a.lse[stat_base + ql], d = a.delta[stat_base + ql];
+            s.lse = q < a.Lq ? l : -INFINITY;
+            s.delta = q < a.Lq ? d : 0.f;
+            s.word = a.csched.bitmaps[(size_t)t * 64 + tid];
+        }
+    };
+    auto issue = [&](const Meta& m, int stage) {
+        lds_u16* base = lds + stage * STAGE;
+        if (m.start >= 0) {
+            issue_tile_loads<D, 2, SWZ_BOTH>(q_rsrc, base, m.start, sq_bytes, wave, lane);
+            issue_tile_loads<D, 2, SWZ_BOTH>(g_rsrc, base + TILE, m.start, so_bytes, wave, lane);
         } else {
-            issue_gather_loads<D, 2, false>(q_rsrc, Qk, gcur, sq_bytes, wave, lane);
-            issue_gather_loads<D, 2, true>(q_rsrc, Qv, gcur, sq_bytes, wave, lane);
-            issue_gather_loads<D, 2, false>(g_rsrc, Gk, gcur, so_bytes, wave, lane);
-            issue_gather_loads<D, 2, true>(g_rsrc, Gv, gcur, so_bytes, wave, lane);
+            issue_gather_loads<D, 2, SWZ_BOTH>(q_rsrc, base, m.gq, sq_bytes, wave, lane);
+            issue_gather_loads<D, 2, SWZ_BOTH>(g_rsrc, base + TILE, m.gq, so_bytes, wave, lane);
         }
-        if (tid < 64) {                                      // per-query statistics and bitmap words
-            const int q = s_cur >= 0 ? s_cur + tid : qmine;
-            const bool ok = q < a.Lq;
-            s_lse2[tid] = ok ? lse2_of(a.lse[stat_base + q]) : INFINITY;
-            s_delta[tid] = ok ? a.delta[stat_base + q] : 0.f;
-            s_word[tid] = a.csched.bitmaps[(size_t)t * 64 + tid];
+    };
+
+    Meta cur, nxt;
+    Stat st;
+    st.lse = -INFINITY;
+    st.delta = 0.f;
+    st.word = 0;
+    if (t0 < t1) {
+        fetch(t0, cur);
+        issue(cur, 0);
+        fetch_stat(t0, cur, st);
+        nxt = cur;
+        if (t0 + 1 < t1) fetch(t0 + 1, nxt);
+    }
+    wait_vmem();
+    settle<KSTEPS>(kreg);
+    settle<KSTEPS>(vreg);
+
+    int stage = 0;
+    for (int t = t0; t < t1; ++t) {
+        wait_vmem();                                         // entry t, its statistics and the metadata of t + 1
+        if (tid < 64) {
+            s_lse2[stage][tid] = lse2_of(st.lse);
+            s_delta[stage][tid] = st.delta;
+            s_word[stage][tid] = st.word;
         }
-        int s_nxt = 0;
+        __syncthreads();                                     // ... for everybody; the other stage is free
         if (t + 1 < t1) {
-            s_nxt = a.csched.start[t + 1];
-            if (s_nxt < 0) load_rows(t + 1, gnext, qmine_next);
+            issue(nxt, stage ^ 1);
+            fetch_stat(t + 1, nxt, st);
+            if (t + 2 < t1) fetch(t + 2, nxt);
         }
-        wait_vmem();
-        __syncthreads();
+        uint16_t* base = smem + stage * STAGE;
         f32x16 sacc[2], pacc[2];
-        qk_64<D>(smem, kreg, n, k_swz, sacc);                // S  = Q K^T   (rows: queries, lane: key)
-        qk_64<D>(smem + 2 * TILE, vreg, n, k_swz, pacc);     // dP = dO V^T
+        qk_64<D>(base, kreg, n, k_swz, sacc);                // S  = Q K^T   (rows: queries, lane: key)
+        qk_64<D>(base + TILE, vreg, n, k_swz, pacc);         // dP = dO V^T
 #pragma unroll
         for (int qblk = 0; qblk < 2; ++qblk)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int r0 = 32 * qblk + 8 * g + 4 * hh;   // 4 consecutive query slots
-                const float4 l4 = *reinterpret_cast<const float4*>(&s_lse2[r0]);
-                const float4 d4 = *reinterpret_cast<const float4*>(&s_delta[r0]);
+                const float4 l4 = *reinterpret_cast<const float4*>(&s_lse2[stage][r0]);
+                const float4 d4 = *reinterpret_cast<const float4*>(&s_delta[stage][r0]);
                 const float le[4] = {l4.x, l4.y, l4.z, l4.w}, de[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int i = 4 * g + e;
-                    const bool kept = (s_word[r0 + e] >> kcol) & 1ull;
+                    const bool kept = (s_word[stage][r0 + e] >> kcol) & 1ull;
                     const float p = kept ? __builtin_amdgcn_exp2f(fmaf(sacc[qblk][i], sc, -le[e])) : 0.f;
                     sacc[qblk][i] = p;                       // P
                     pacc[qblk][i] = p * (pacc[qblk][i] - de[e]);   // dS
                 }
             }
-        tr_mm_64<D>(Gv, sacc, dvacc, tr);                    // dV^T += dO^T P
-        tr_mm_64<D>(Qv, pacc, dkacc, tr);                    // dK^T += Q^T dS
-        s_cur = s_nxt;
-        qmine = qmine_next;
-#pragma unroll
-        for (int u = 0; u < NLOAD; ++u) gcur[u] = gnext[u];
+        tr_mm_64_u<D>(lds + stage * STAGE + TILE, sacc, dvacc, tr);   // dV^T += dO^T P
+        tr_mm_64_u<D>(lds + stage * STAGE, pacc, dkacc, tr);          // dK^T += Q^T dS
+        stage ^= 1;
     }
     __syncthreads();                                         // all wavefronts are done with the tiles
     const int krow0 = kb * 64 + wave * 32;
-    uint16_t* stage = smem + wave * 32 * D;
-    store_rows_bf16<D>(stage, dkacc, a.scale, lane, dKp + (size_t)krow0 * a.sk[2], a.sk[2], a.Lk - krow0);
+    uint16_t* stg = smem + wave * 32 * D;
+    store_rows_bf16<D>(stg, dkacc, a.scale, lane, dKp + (size_t)krow0 * a.sk[2], a.sk[2], a.Lk - krow0);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // the staging area is reused
-    store_rows_bf16<D>(stage, dvacc, 1.0f, lane, dVp + (size_t)krow0 * a.sv[2], a.sv[2], a.Lk - krow0);
+    store_rows_bf16<D>(stg, dvacc, 1.0f, lane, dVp + (size_t)krow0 * a.sv[2], a.sv[2], a.Lk - krow0);
 }
 
 template <int D>

@@ -7,7 +7,8 @@
 // folded in.  Same structure as the row schedule with the roles of rows and columns swapped.
 //
 // One wavefront per block column, one lane per tile row; all control flow depends on ballots
-// only, so the emitted order is fixed: no atomics.
+// only, so the emitted order is fixed: no atomics.  A second kernel appends, behind the entry
+// counts, the order in which the dK/dV kernel should visit the block columns of each head.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -77,6 +78,35 @@ __global__ __launch_bounds__(64) void build_col_schedule_kernel(
     if (lane == 0) s.cnt[c] = n_out;
 }
 
+// Visiting order of the block columns of one head: columns with at least twice the head's mean
+// number of entries ("heavy": their workgroups run longest and should start first) in ascending
+// order, then the others in ascending order.  One wavefront per head.
+//   order  [H*nKB]  block column at each position      n_heavy [H]  number of heavy columns
+__global__ __launch_bounds__(64) void col_order_kernel(const int32_t* __restrict__ cnt, int nKB,
+                                                       int32_t* __restrict__ order, int32_t* __restrict__ n_heavy)
+{
+    const int h = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int32_t* c = cnt + (size_t)h * nKB;
+    long long sum = 0;
+    for (int k = lane; k < nKB; k += 64) sum += c[k];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    const long long limit = (2 * sum + nKB - 1) / nKB;       // ceil(2 * mean)
+    int pos = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int k0 = 0; k0 < nKB; k0 += 64) {
+            const int k = k0 + lane;
+            const bool heavy = k < nKB && c[k] >= limit && c[k] > 1;
+            const bool take = k < nKB && heavy == (pass == 0);
+            const unsigned long long m = __ballot(take);
+            if (take) order[(size_t)h * nKB + pos + __popcll(m & ((1ull << lane) - 1ull))] = k;
+            pos += __popcll(m);
+        }
+        if (pass == 0 && lane == 0) n_heavy[h] = pos;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_build_col_schedule(const int32_t* col_ptr, const int32_t* row_idx, const int32_t* tile_idx,
@@ -86,6 +116,11 @@ hipError_t launch_build_col_schedule(const int32_t* col_ptr, const int32_t* row_
     const int nKB = (Lk + 63) / 64;
     hipLaunchKernelGGL(build_col_schedule_kernel, dim3((unsigned)(H * nKB)), dim3(64), 0, stream, col_ptr,
                        row_idx, tile_idx, bitmaps, nKB, Lq, Lk, causal, min_rows, s);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    int32_t* order = s.cnt + (size_t)H * nKB;                // the count array carries the visiting order
+    hipLaunchKernelGGL(col_order_kernel, dim3((unsigned)H), dim3(64), 0, stream, s.cnt, nKB, order,
+                       order + (size_t)H * nKB);
     return hipGetLastError();
 }
 

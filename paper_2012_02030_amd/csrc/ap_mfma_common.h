@@ -28,6 +28,20 @@ template <int D> __device__ __forceinline__ int swz_v(int r)
     return D == 128 ? 4 * (r & 3) : (D == 64 ? 4 * ((r >> 1) & 1) : 0);
 }
 
+// One swizzle that serves both kinds of read, for tiles that are read row-wise and through the
+// transposing load: a bijection on r % 16 (r % 8 for D = 64, (r / 4) % 4 for D = 32) as the
+// row-wise reads need, whose upper chunk bits follow the low row bits as the transposing reads need.
+template <int D> __device__ __forceinline__ int swz_u(int r)
+{
+    return D == 128 ? (((r & 3) << 2) | ((r >> 2) & 3))
+                    : (D == 64 ? ((((r >> 1) & 1) << 2) | ((r >> 2) & 3)) : ((r >> 2) & 3));
+}
+enum { SWZ_KEY = 0, SWZ_VALUE = 1, SWZ_BOTH = 2 };
+template <int D, int S> __device__ __forceinline__ int swz(int r)
+{
+    return S == SWZ_KEY ? swz_k<D>(r) : (S == SWZ_VALUE ? swz_v<D>(r) : swz_u<D>(r));
+}
+
 __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
 {
     uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
@@ -73,8 +87,9 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned num_bytes
 __device__ __forceinline__ unsigned lds_addr_of(lds_u16* p) { return (unsigned)(uintptr_t)p; }
 
 // Issue the loads of one 64-row tile (rows row0.. of a [rows, D] bf16 slice described by the
-// buffer resource) into LDS.  Every wavefront instruction moves 64 x 16 bytes = 1 KB.
-template <int D, int NW, bool IS_V>
+// buffer resource) into LDS with swizzle S (SWZ_KEY, SWZ_VALUE or SWZ_BOTH).  Every wavefront
+// instruction moves 64 x 16 bytes = 1 KB.
+template <int D, int NW, int S>
 __device__ __forceinline__ void issue_tile_loads(rsrc_t rsrc, lds_u16* dst, int row0,
                                                  int stride_bytes, int wave, int lane)
 {
@@ -88,7 +103,7 @@ __device__ __forceinline__ void issue_tile_loads(rsrc_t rsrc, lds_u16* dst, int 
     for (int u = 0; u < NI / NW; ++u) {
         const int j = wave + NW * u;
         const int r = j * RPI + rl;           // row inside the tile
-        const int c = cp ^ (IS_V ? swz_v<D>(r) : swz_k<D>(r));
+        const int c = cp ^ swz<D, S>(r);
         const int voff = rl * stride_bytes + c * 16;
         const int soff = (row0 + j * RPI) * stride_bytes;
         load16_to_lds(lds_addr_of(dst + j * 512), voff, rsrc, soff);
@@ -97,7 +112,7 @@ __device__ __forceinline__ void issue_tile_loads(rsrc_t rsrc, lds_u16* dst, int 
 
 // Same for a gathered entry: row u of this lane's instructions comes from key gidx[u]
 // (an empty slot holds Lk, which lies beyond num_records and reads as zeros).
-template <int D, int NW, bool IS_V>
+template <int D, int NW, int S>
 __device__ __forceinline__ void issue_gather_loads(rsrc_t rsrc, lds_u16* dst, const int* gidx,
                                                    int stride_bytes, int wave, int lane)
 {
@@ -110,7 +125,7 @@ __device__ __forceinline__ void issue_gather_loads(rsrc_t rsrc, lds_u16* dst, co
     for (int u = 0; u < NI / NW; ++u) {
         const int j = wave + NW * u;
         const int r = j * RPI + rl;
-        const int c = cp ^ (IS_V ? swz_v<D>(r) : swz_k<D>(r));
+        const int c = cp ^ swz<D, S>(r);
         const int voff = gidx[u] * stride_bytes + c * 16;
         load16_to_lds(lds_addr_of(dst + j * 512), voff, rsrc, 0);
     }
@@ -213,6 +228,53 @@ __device__ __forceinline__ void tr_mm_64(lds_u16* Ts, const f32x16* p, f32x16* a
             lds_u16* p0 = Ts + (16 * ks + t.lane_row) * D + chunk * 8 + t.in_chunk;
             const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p0);
             const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 8 * D));
+            treg[db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    };
+    bf16x8 tcur[DBLK], tnext[DBLK];
+    read_t(0, tcur);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        bf16x8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[e] = (__bf16)p[ks >> 1][8 * (ks & 1) + e];
+        if (ks + 1 < 4) read_t(ks + 1, tnext);
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db)
+            acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tcur[db], pb, acc[db], 0, 0, 0);
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) tcur[db] = tnext[db];
+    }
+}
+
+// The same product for a tile stored with the swizzle SWZ_BOTH.
+template <int D>
+struct TrReadU {
+    int off[2][D / 32];      // element offsets of this lane's two reads of every 32-column block
+};
+template <int D>
+__device__ __forceinline__ TrReadU<D> make_tr_read_u(int lane)
+{
+    const int hh = lane >> 5, i16 = lane & 15, g = (lane >> 4) & 1, vj = i16 >> 2;
+    const int lane_row = 4 * hh + vj, in_chunk = 4 * (i16 & 1), chunk_lo = 2 * g + ((i16 >> 1) & 1);
+    const int fx = swz_u<D>(lane_row);                       // row + 8 flips bit 1 of the swizzle
+    TrReadU<D> t;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+        t.off[0][db] = lane_row * D + ((4 * db + chunk_lo) ^ fx) * 8 + in_chunk;
+        t.off[1][db] = (lane_row + 8) * D + ((4 * db + chunk_lo) ^ fx ^ 2) * 8 + in_chunk;
+    }
+    return t;
+}
+template <int D>
+__device__ __forceinline__ void tr_mm_64_u(lds_u16* Ts, const f32x16* p, f32x16* acc, const TrReadU<D>& t)
+{
+    constexpr int DBLK = D / 32;
+    auto read_t = [&](int ks, bf16x8* treg) {
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) {
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(Ts + 16 * ks * D + t.off[0][db]));
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(Ts + 16 * ks * D + t.off[1][db]));
             treg[db] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         }
     };

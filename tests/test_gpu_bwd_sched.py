@@ -39,6 +39,15 @@ def check_col_schedule(mask, causal, min_rows):
     cols, words = cs.cols.cpu().numpy(), cs.bitmaps.cpu().numpy().view(np.uint64)
     vis = visible_mask(mask, causal)
     nKB = -(-Lk // 64)
+    # behind the counts: every head's visiting order (columns with >= twice the mean count first)
+    order = cnt[H * nKB:2 * H * nKB].reshape(H, nKB)
+    n_heavy = cnt[2 * H * nKB:]
+    cnt = cnt[:H * nKB]
+    for h in range(H):
+        ch = cnt[h * nKB:(h + 1) * nKB]
+        heavy = (ch * nKB >= 2 * ch.sum()) & (ch > 1)
+        assert n_heavy[h] == heavy.sum()
+        assert np.array_equal(order[h], np.concatenate([np.nonzero(heavy)[0], np.nonzero(~heavy)[0]]))
     pad = np.zeros((H, Lq, nKB * 64), bool)
     pad[:, :, :Lk] = vis
     want_words = np.zeros((H, Lq, nKB), np.uint64)
@@ -141,6 +150,19 @@ def test_scheduled_backward_any_packing(mins):
     mask = synth.random_mask(2, 260, 330, 0.06, seed=77)
     mask[:, 100:180, 64:128] = 1                     # a few dense tiles among sparse ones
     run_bwd_sched(Q, K, V, dO, mask, True, min_cols=mins[0], min_rows=mins[1])
+
+
+@pytest.mark.parametrize("B,H", [(2, 4), (8, 2), (1, 8)])
+def test_scheduled_backward_heavy_columns_first(B, H):
+    """B * H divisible by 8: the dK/dV workgroups take the heavy block columns of all their pairs
+    first.  One or two key blocks that every query attends to are such columns."""
+    Lq = Lk = 448
+    Q, K, V, dO = rand_inputs(33 + B, B, H, Lq, Lk, 64)
+    mask = synth.random_mask(H, Lq, Lk, 0.01, seed=5)
+    mask[:, :, 0:64] = 1
+    mask[1::2, :, 128:192] = 1
+    run_bwd_sched(Q, K, V, dO, mask, True)
+    run_bwd_sched(Q, K, V, dO, mask, False)
 
 
 def test_scheduled_backward_on_the_structured_masks():
