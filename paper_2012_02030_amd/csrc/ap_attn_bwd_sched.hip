@@ -171,7 +171,7 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * STAGE];
     __shared__ __attribute__((aligned(16))) float s_lse2[2][64];
     __shared__ __attribute__((aligned(16))) float s_delta[2][64];
-    __shared__ __attribute__((aligned(16))) uint64_t s_word[2][64];
+    __shared__ __attribute__((aligned(16))) uint32_t s_half[2][2][64];   // bitmap words: low halves, high halves
     lds_u16* lds = (lds_u16*)smem;
 
     const int tid = threadIdx.x;
@@ -244,7 +244,6 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     const float sc = a.scale * kLog2e;
     const int k_swz = hh ^ swz_u<D>(n);
     const TrReadU<D> tr = make_tr_read_u<D>(lane);
-    const int kcol = wave * 32 + n;                          // this lane's key inside the block column
 
     f32x16 dkacc[DBLK], dvacc[DBLK];
 #pragma unroll
@@ -321,7 +320,8 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
         if (tid < 64) {
             s_lse2[stage][tid] = lse2_of(st.lse);
             s_delta[stage][tid] = st.delta;
-            s_word[stage][tid] = st.word;
+            s_half[stage][0][tid] = (uint32_t)st.word;
+            s_half[stage][1][tid] = (uint32_t)(st.word >> 32);
         }
         __syncthreads();                                     // ... for everybody; the other stage is free
         if (t + 1 < t1) {
@@ -333,6 +333,7 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
         f32x16 sacc[2], pacc[2];
         qk_64<D>(base, kreg, n, k_swz, sacc);                // S  = Q K^T   (rows: queries, lane: key)
         qk_64<D>(base + TILE, vreg, n, k_swz, pacc);         // dP = dO V^T
+        const uint32_t* halves = &s_half[stage][wave][0];    // this wavefront's 32 keys: bit n of these
 #pragma unroll
         for (int qblk = 0; qblk < 2; ++qblk)
 #pragma unroll
@@ -340,12 +341,16 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
                 const int r0 = 32 * qblk + 8 * g + 4 * hh;   // 4 consecutive query slots
                 const float4 l4 = *reinterpret_cast<const float4*>(&s_lse2[stage][r0]);
                 const float4 d4 = *reinterpret_cast<const float4*>(&s_delta[stage][r0]);
+                const uint4 w4 = *reinterpret_cast<const uint4*>(&halves[r0]);
                 const float le[4] = {l4.x, l4.y, l4.z, l4.w}, de[4] = {d4.x, d4.y, d4.z, d4.w};
+                const uint32_t we[4] = {w4.x, w4.y, w4.z, w4.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int i = 4 * g + e;
-                    const bool kept = (s_word[stage][r0 + e] >> kcol) & 1ull;
-                    const float p = kept ? __builtin_amdgcn_exp2f(fmaf(sacc[qblk][i], sc, -le[e])) : 0.f;
+                    // pruned entries: the exponent's argument is replaced by -inf with a bit-select
+                    const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)we[e], n, 1);
+                    const float x = fmaf(sacc[qblk][i], sc, -le[e]);
+                    const float p = __builtin_amdgcn_exp2f(__uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep)));
                     sacc[qblk][i] = p;                       // P
                     pacc[qblk][i] = p * (pacc[qblk][i] - de[e]);   // dS
                 }
