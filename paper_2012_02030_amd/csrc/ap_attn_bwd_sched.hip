@@ -189,26 +189,33 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     const int NP = a.B * a.H;
     int pair, idx;
     if (NP % 8 == 0 && NP / 8 <= 64) {
+        // lane p looks at pair P0 + p: one load and two wave-wide prefix sums instead of a chain of
+        // dependent scalar loads
         const int PP = NP / 8, P0 = (blockIdx.x & 7) * PP;
-        int l = blockIdx.x >> 3;
-        pair = -1;
-        idx = 0;
-        for (int p = 0; p < PP && pair < 0; ++p) {
-            const int hv = n_heavy[(P0 + p) % a.H];
-            if (l < hv) {
-                pair = P0 + p;
-                idx = l;
+        const int l = blockIdx.x >> 3;
+        const int hv = lane < PP ? n_heavy[(P0 + lane) % a.H] : 0;
+        const int lt = lane < PP ? nKB - hv : 0;
+        int hv_incl = hv, lt_incl = lt;                      // inclusive prefix sums over the lanes
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int x = __shfl_up(hv_incl, o, 64), y = __shfl_up(lt_incl, o, 64);
+            if (lane >= o) {
+                hv_incl += x;
+                lt_incl += y;
             }
-            l -= hv;
         }
-        for (int p = 0; p < PP && pair < 0; ++p) {
-            const int hv = n_heavy[(P0 + p) % a.H];
-            if (l < nKB - hv) {
-                pair = P0 + p;
-                idx = hv + l;
-            }
-            l -= nKB - hv;
-        }
+        const int hv_total = __shfl(hv_incl, 63, 64);
+        const bool in_heavy = l < hv_total;
+        const int ll = in_heavy ? l : l - hv_total;
+        const int incl = in_heavy ? hv_incl : lt_incl, mine = in_heavy ? hv : lt;
+        // the lane whose range [incl - mine, incl) holds ll
+        const unsigned long long hit = __ballot(lane < PP && ll >= incl - mine && ll < incl);
+        if (hit == 0) return;                                // cannot happen for grid = pairs x columns
+        const int p = __ffsll((long long)hit) - 1;           // exactly one lane
+        pair = P0 + p;
+        idx = ll - (__shfl(incl, p, 64) - __shfl(mine, p, 64)) + (in_heavy ? 0 : __shfl(hv, p, 64));
+        pair = __builtin_amdgcn_readfirstlane(pair);
+        idx = __builtin_amdgcn_readfirstlane(idx);
     } else {
         const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
         pair = bid / nKB;
