@@ -40,6 +40,11 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB
     const int lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
     const int g_row = lane / (D / 8);
+    // A zero the compiler cannot see through.  Indexing with it turns the per-entry load of a
+    // start into a vector load: a scalar load inside the loop would make every later wait for an
+    // LDS read (same counter, scalar loads return out of order) wait for memory as well.
+    int vzero = 0;
+    asm volatile("" : "+v"(vzero));
 
     const int bid = xcd_contiguous(blockIdx.x, gridDim.x);
     const int qb = nQB - 1 - (bid % nQB);
@@ -86,27 +91,30 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB
     const int t0 = a.row_ptr[r];
     const int t1 = t0 + a.sched.cnt[r];
 
-    // metadata of an entry: where it starts (or -1), the gather keys of the rows this lane loads
-    // (read for every entry, used by gathered ones only) and this lane's bitmap word
+    // metadata of an entry: where it starts (or -1), gather key `lane` (read for every entry,
+    // used by gathered ones only) and this lane's bitmap word: three loads per entry
     struct Meta {
         int start;
-        int gk[NLOAD];
+        int key;
         uint64_t word;
     };
     auto fetch = [&](int t, Meta& m) {
-        m.start = a.sched.start[t];
-#pragma unroll
-        for (int u = 0; u < NLOAD; ++u) m.gk[u] = a.sched.cols[(size_t)t * 64 + (wave + 2 * u) * RPI + g_row];
+        m.start = a.sched.start[t + vzero];                  // a vector load: see vzero
+        m.key = a.sched.cols[(size_t)t * 64 + lane];
         m.word = a.sched.bitmaps[(size_t)t * 64 + brow];     // causal limit folded in
     };
     auto issue = [&](const Meta& m, int stage) {
         lds_u16* base = lds + stage * STAGE;
-        if (m.start >= 0) {
-            issue_tile_loads<D, 2, SWZ_BOTH>(k_rsrc, base, m.start, sk_bytes, wave, lane);
-            issue_tile_loads<D, 2, SWZ_BOTH>(v_rsrc, base + TILE, m.start, sv_bytes, wave, lane);
+        const int start = __builtin_amdgcn_readfirstlane(m.start);
+        if (start >= 0) {
+            issue_tile_loads<D, 2, SWZ_BOTH>(k_rsrc, base, start, sk_bytes, wave, lane);
+            issue_tile_loads<D, 2, SWZ_BOTH>(v_rsrc, base + TILE, start, sv_bytes, wave, lane);
         } else {
-            issue_gather_loads<D, 2, SWZ_BOTH>(k_rsrc, base, m.gk, sk_bytes, wave, lane);
-            issue_gather_loads<D, 2, SWZ_BOTH>(v_rsrc, base + TILE, m.gk, sv_bytes, wave, lane);
+            int gk[NLOAD];                                   // keys of the rows this lane loads
+#pragma unroll
+            for (int u = 0; u < NLOAD; ++u) gk[u] = __shfl(m.key, (wave + 2 * u) * RPI + g_row, 64);
+            issue_gather_loads<D, 2, SWZ_BOTH>(k_rsrc, base, gk, sk_bytes, wave, lane);
+            issue_gather_loads<D, 2, SWZ_BOTH>(v_rsrc, base + TILE, gk, sv_bytes, wave, lane);
         }
     };
 
@@ -179,6 +187,11 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     const int lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
     const int g_row = lane / (D / 8);
+    // A zero the compiler cannot see through.  Indexing with it turns the per-entry load of a
+    // start into a vector load: a scalar load inside the loop would make every later wait for an
+    // LDS read (same counter, scalar loads return out of order) wait for memory as well.
+    int vzero = 0;
+    asm volatile("" : "+v"(vzero));
 
     // Which (example, head) pair and which position of the head's visiting order this workgroup
     // takes.  Every XCD gets a contiguous range of pairs (they share Q and dO rows in its L2); when
@@ -265,13 +278,11 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     const int t0 = a.col_ptr[c];
     const int t1 = t0 + a.csched.cnt[c];
 
-    // metadata of an entry: where it starts (or -1), the gathered queries of the rows this lane
-    // loads and of the slot whose statistics this thread fetches (read for every entry, used by
-    // gathered ones only)
+    // metadata of an entry: where it starts (or -1) and gathered query `lane` (read for every
+    // entry, used by gathered ones only)
     struct Meta {
         int start;
-        int gq[NLOAD];
-        int mine;
+        int row;
     };
     // per-slot statistics of an entry, fetched by the first 64 threads one step ahead
     struct Stat {
@@ -279,14 +290,12 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
         uint64_t word;
     };
     auto fetch = [&](int t, Meta& m) {
-        m.start = a.csched.start[t];
-#pragma unroll
-        for (int u = 0; u < NLOAD; ++u) m.gq[u] = a.csched.cols[(size_t)t * 64 + (wave + 2 * u) * RPI + g_row];
-        m.mine = tid < 64 ? a.csched.cols[(size_t)t * 64 + tid] : 0;
+        m.start = a.csched.start[t + vzero];                 // a vector load: see vzero
+        m.row = a.csched.cols[(size_t)t * 64 + lane];
     };
     auto fetch_stat = [&](int t, const Meta& m, Stat& s) {
         if (tid < 64) {
-            const int q = m.start >= 0 ? m.start + tid : m.mine;
+            const int q = m.start >= 0 ? m.start + tid : m.row;   // (all lanes hold the same start)
             const int ql = q < a.Lq ? q : a.Lq - 1;
             const float l = a.lse[stat_base + ql], d = a.delta[stat_base + ql];
             s.lse = q < a.Lq ? l : -INFINITY;
@@ -296,12 +305,16 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     };
     auto issue = [&](const Meta& m, int stage) {
         lds_u16* base = lds + stage * STAGE;
-        if (m.start >= 0) {
-            issue_tile_loads<D, 2, SWZ_BOTH>(q_rsrc, base, m.start, sq_bytes, wave, lane);
-            issue_tile_loads<D, 2, SWZ_BOTH>(g_rsrc, base + TILE, m.start, so_bytes, wave, lane);
+        const int start = __builtin_amdgcn_readfirstlane(m.start);
+        if (start >= 0) {
+            issue_tile_loads<D, 2, SWZ_BOTH>(q_rsrc, base, start, sq_bytes, wave, lane);
+            issue_tile_loads<D, 2, SWZ_BOTH>(g_rsrc, base + TILE, start, so_bytes, wave, lane);
         } else {
-            issue_gather_loads<D, 2, SWZ_BOTH>(q_rsrc, base, m.gq, sq_bytes, wave, lane);
-            issue_gather_loads<D, 2, SWZ_BOTH>(g_rsrc, base + TILE, m.gq, so_bytes, wave, lane);
+            int gq[NLOAD];                                   // queries of the rows this lane loads
+#pragma unroll
+            for (int u = 0; u < NLOAD; ++u) gq[u] = __shfl(m.row, (wave + 2 * u) * RPI + g_row, 64);
+            issue_gather_loads<D, 2, SWZ_BOTH>(q_rsrc, base, gq, sq_bytes, wave, lane);
+            issue_gather_loads<D, 2, SWZ_BOTH>(g_rsrc, base + TILE, gq, so_bytes, wave, lane);
         }
     };
 
