@@ -18,7 +18,7 @@ The backward pass (gradients of the masked-attention equation) is in ``backward.
 masked_attention_backward.
 
 Masked attention with the 1.5-entmax normaliser of Section 6 is in ``entmax.py`` (numpy): entmax15,
-masked_entmax15_attention.
+masked_entmax15_attention and their gradients (entmax15_backward, masked_entmax15_attention_backward).
 
 Mask construction (Section 3.2, Eq. (1) and Eq. (2)) is in ``mask_construction.py`` (numpy):
 attention_maps, mean_attention_map, percentile_threshold, prune_mask.
@@ -32,7 +32,8 @@ import subprocess
 import numpy as np
 
 from .backward import masked_attention_backward  # noqa: F401
-from .entmax import entmax15, masked_entmax15_attention  # noqa: F401
+from .entmax import (entmax15, entmax15_backward, masked_entmax15_attention,  # noqa: F401
+                     masked_entmax15_attention_backward)
 from .mask_construction import (attention_maps, mean_attention_map,  # noqa: F401
                                 percentile_threshold, prune_mask)
 

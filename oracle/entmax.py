@@ -17,6 +17,18 @@ the support is right iff  x_(k) > tau >= x_(k+1); the largest k with x_(k) > tau
 support.  Plain numpy, one row at a time.
 
 masked_entmax15_attention   O = entmax_1.5(scale * Q K^T restricted to kept, visible keys) V
+
+Backward (the models of Section 6 are trained with this activation).  The paper prints no
+gradient; from the conditions above, with u_j = [z_j/2 - tau]_+ (so p_j = u_j^2) and sum_j p_j = 1
+held fixed:  dp_j = 2 u_j (dz_j / 2 - dtau)  and  sum_j u_j (dz_j / 2 - dtau) = 0,  hence
+
+    dtau = sum_j u_j dz_j / (2 sum_j u_j),
+    dL/dz_j = u_j (g_j - gbar),   g_j = dL/dp_j,   gbar = sum_k u_k g_k / sum_k u_k
+
+on the support and 0 outside it.
+
+entmax15_backward                   dL/dz for one score vector
+masked_entmax15_attention_backward  dQ, dK, dV of masked_entmax15_attention's O
 """
 from __future__ import annotations
 
@@ -70,3 +82,46 @@ def masked_entmax15_attention(Q, K, V, mask, causal: bool = False, scale: float 
                 O[b, h, i] = p @ V[b, h, cols]
                 tau[b, h, i] = t
     return O, tau
+
+
+def entmax15_backward(z: np.ndarray, g: np.ndarray) -> np.ndarray:
+    """dL/dz of p = entmax15(z) for an upstream gradient g = dL/dp (1-D, fp64)."""
+    z = np.asarray(z, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    _, tau = entmax15(z)
+    u = np.maximum(z / 2.0 - tau, 0.0)
+    gbar = float(u @ g) / float(u.sum())
+    return u * (g - gbar)
+
+
+def masked_entmax15_attention_backward(Q, K, V, mask, dO, causal: bool = False, scale: float = 0.0):
+    """Gradients (dQ, dK, dV) of masked_entmax15_attention's O for an upstream gradient dO, fp64.
+
+    With s_ij = scale <Q_i, K_j> on kept, visible entries, P_i = entmax15(s_i) and O_i = sum_j P_ij V_j:
+    dV_j = sum_i P_ij dO_i,  g_ij = <dO_i, V_j>,  dS_i = entmax15_backward(s_i, g_i),
+    dQ_i = scale sum_j dS_ij K_j,  dK_j = scale sum_i dS_ij Q_i.  Queries without a kept key
+    contribute nothing.
+    """
+    Q, K, V, dO = (np.asarray(x, dtype=np.float64) for x in (Q, K, V, dO))
+    keep = np.asarray(mask) != 0
+    B, H, Lq, D = Q.shape
+    Lk = K.shape[2]
+    if scale <= 0:
+        scale = 1.0 / math.sqrt(D)
+    if causal:
+        keep = keep & (np.arange(Lk)[None, :] <= np.arange(Lq)[:, None] + (Lk - Lq))[None]
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    for b in range(B):
+        for h in range(H):
+            S = (Q[b, h] @ K[b, h].T) * scale
+            G = dO[b, h] @ V[b, h].T
+            for i in range(Lq):
+                cols = np.flatnonzero(keep[h, i])
+                if cols.size == 0:
+                    continue
+                p, _ = entmax15(S[i, cols])
+                ds = entmax15_backward(S[i, cols], G[i, cols])
+                dV[b, h, cols] += np.outer(p, dO[b, h, i])
+                dQ[b, h, i] = scale * (ds @ K[b, h, cols])
+                dK[b, h, cols] += scale * np.outer(ds, Q[b, h, i])
+    return dQ, dK, dV
