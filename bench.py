@@ -513,9 +513,24 @@ def main():
         ent_ms = timed(lambda: ap.ap_sparse_attn_entmax15_fwd(q, k, v, lay, causal=cfg.causal, out=out,
                                                                sched=sched), steps)
         soft_ms = timed(lambda: ap.ap_sparse_attn_fwd(q, k, v, lay, causal=cfg.causal, out=out, sched=sched), steps)
+        # backward pass of the same call (row and column schedules) next to the softmax backward pass
+        lt = ap.ap_build_layout_transpose(lay)
+        cs = ap.ap_build_col_schedule(lay, lt, causal=cfg.causal)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(synth.SEED + 78)
+        g = torch.randn(q.shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        _, tau = ap.ap_sparse_attn_entmax15_fwd(q, k, v, lay, causal=cfg.causal, sched=sched)
+        O, lse = ap.ap_sparse_attn_fwd(q, k, v, lay, causal=cfg.causal, sched=sched)
+        ent_bwd_ms = timed(lambda: ap.ap_sparse_attn_entmax15_bwd(q, k, v, g, tau, lay, lt, sched, cs,
+                                                                  causal=cfg.causal), steps)
+        soft_bwd_ms = timed(lambda: ap.ap_sparse_attn_bwd(q, k, v, O, g, lse, lay, lt, causal=cfg.causal,
+                                                          sched=sched, col_sched=cs), steps)
         kept = int(mask_np.sum())
         tiles = int(lay.nnz.item())
         return {
+            "backward_ms": ent_bwd_ms,
+            "softmax_backward_same_schedules_ms": soft_bwd_ms,
+            "backward_kept_tflops": 10.0 * cfg.D * kept * cfg.B / (ent_bwd_ms * 1e-3) / 1e12,
             "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D, "causal": cfg.causal},
             "tiles_stored": tiles,
             "entries_visited": int(sched.cnt.sum().item()),

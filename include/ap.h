@@ -331,6 +331,43 @@ ap_status ap_sparse_attn_bwd_sched(const void *Q, const void *K, const void *V, 
                                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Backward pass of ap_sparse_attn_entmax15_fwd (Section 6: the models there are trained with the
+ * 1.5-entmax normaliser under the pruning mask).
+ *
+ * With x_ij, tau and p_ij as in ap_sparse_attn_entmax15_fwd, u_ij = max(x_ij - tau_i, 0) (so
+ * p_ij = u_ij^2) and g_ij = <dO[b,h,i,:], V[b,h,j,:]>, holding sum_j p_ij = 1 fixed:
+ *
+ *     gbar_i      = sum_j u_ij g_ij / sum_j u_ij
+ *     dS_ij       = u_ij (g_ij - gbar_i)                 (gradient with respect to scale * <Q_i, K_j>)
+ *     dV[b,h,j,:] = sum_i p_ij dO[b,h,i,:]
+ *     dQ[b,h,i,:] = scale sum_j dS_ij K[b,h,j,:]         dK[b,h,j,:] = scale sum_i dS_ij Q[b,h,i,:]
+ *
+ *   Q, K, V, dO   as in ap_sparse_attn_bwd (dO uses stride_o); O is not needed
+ *   tau           float [B, H, Lq] contiguous, the forward call's output (required)
+ *   sched, col_sched   the row schedule and the column schedule of the layout (both required,
+ *                 built with the same `causal`)
+ *   workspace     device scratch of at least ap_entmax15_bwd_workspace_bytes(B, H, Lq) bytes,
+ *                 16-byte aligned (gbar)
+ *   everything else as in ap_sparse_attn_bwd_sched
+ *
+ * Supported: dtype = AP_BF16, D in {32, 64, 128}, block_m = block_n = 64.  Three launches (gbar,
+ * dQ, dK/dV).  Deterministic.
+ * ------------------------------------------------------------------------------------------- */
+size_t ap_entmax15_bwd_workspace_bytes(int B, int H, int Lq);
+
+ap_status ap_sparse_attn_entmax15_bwd(const void *Q, const void *K, const void *V, const void *dO,
+                                      const float *tau, void *dQ, void *dK, void *dV, ap_dtype dtype,
+                                      int B, int H, int Lq, int Lk, int D, const int64_t *stride_q,
+                                      const int64_t *stride_k, const int64_t *stride_v,
+                                      const int64_t *stride_o, const int32_t *row_ptr,
+                                      const int32_t *col_idx, const uint64_t *bitmaps,
+                                      const int32_t *col_ptr, const int32_t *row_idx,
+                                      const int32_t *tile_idx, int block_m, int block_n,
+                                      const ap_schedule *sched, const ap_schedule *col_sched, int causal,
+                                      float softmax_scale, void *workspace, size_t workspace_bytes,
+                                      void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Mask construction, step 1: accumulate attention matrices into the mean map (Section 3.2,
  * Eq. (1)).
  *

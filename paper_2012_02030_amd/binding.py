@@ -29,6 +29,7 @@ SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes
            "ap_sparse_attn_entmax15_fwd", "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
            "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
            "ap_build_col_schedule", "ap_sparse_attn_bwd_sched",
+           "ap_entmax15_bwd_workspace_bytes", "ap_sparse_attn_entmax15_bwd",
            "ap_attention_maps_workspace_bytes", "ap_accumulate_attention_maps",
            "ap_prune_mask_workspace_bytes", "ap_prune_mask")
 
@@ -104,6 +105,12 @@ def lib() -> ctypes.CDLL:
         L.ap_sparse_attn_bwd_sched.argtypes = [vp] * 9 + [i32] * 6 + [ctypes.POINTER(i64)] * 4 + [vp] * 6 + \
                                               [i32, i32, ctypes.POINTER(_CSchedule), ctypes.POINTER(_CSchedule),
                                                i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
+        L.ap_entmax15_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.ap_entmax15_bwd_workspace_bytes.argtypes = [i32] * 3
+        L.ap_sparse_attn_entmax15_bwd.restype = i32
+        L.ap_sparse_attn_entmax15_bwd.argtypes = [vp] * 8 + [i32] * 6 + [ctypes.POINTER(i64)] * 4 + [vp] * 6 + \
+                                                 [i32, i32, ctypes.POINTER(_CSchedule), ctypes.POINTER(_CSchedule),
+                                                  i32, ctypes.c_float, vp, ctypes.c_size_t, vp]
         L.ap_attention_maps_workspace_bytes.restype = ctypes.c_size_t
         L.ap_attention_maps_workspace_bytes.argtypes = [i32] * 3
         L.ap_accumulate_attention_maps.restype = i32
@@ -445,6 +452,49 @@ def ap_sparse_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: tor
                                             ctypes.byref(ccs) if ccs is not None else None, *tail)
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_bwd")
+    return dQ, dK, dV
+
+
+def ap_entmax15_bwd_workspace_bytes(B: int, H: int, Lq: int) -> int:
+    return int(lib().ap_entmax15_bwd_workspace_bytes(B, H, Lq))
+
+
+def ap_sparse_attn_entmax15_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, dO: torch.Tensor,
+                                tau: torch.Tensor, layout: Layout, layout_t: LayoutT, sched: Schedule,
+                                col_sched: Schedule, causal: bool = False, softmax_scale: float = 0.0,
+                                stream: Optional[torch.cuda.Stream] = None):
+    """Gradients (dQ, dK, dV) of ap_sparse_attn_entmax15_fwd's O with respect to Q, K, V (bf16).
+
+    tau is the forward call's second output; both schedules are required.  Asynchronous on the stream."""
+    for t in (Q, K, V, dO):
+        if t.dtype != torch.bfloat16 or t.dim() != 4 or t.stride(3) != 1:
+            raise ValueError("Q, K, V, dO must be bfloat16 [B, H, L, D] with a contiguous last dimension")
+    B, H, Lq, D = Q.shape
+    Lk = K.shape[2]
+    if tuple(K.shape) != (B, H, Lk, D) or tuple(V.shape) != (B, H, Lk, D) or tuple(dO.shape) != (B, H, Lq, D):
+        raise ValueError("shape mismatch")
+    if (H, Lq, Lk) != (layout.H, layout.Lq, layout.Lk):
+        raise ValueError("layout was built for other sizes")
+    for sc in (sched, col_sched):
+        if sc.causal != bool(causal):
+            raise ValueError("schedule was built with another `causal`")
+    tau = tau.contiguous()
+    dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    dK = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device)
+    dV = torch.empty_strided(V.shape, V.stride(), dtype=V.dtype, device=V.device)
+    ws_bytes = ap_entmax15_bwd_workspace_bytes(B, H, Lq)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=Q.device)
+    cs, ccs = sched.c_struct(), col_sched.c_struct()
+    st = lib().ap_sparse_attn_entmax15_bwd(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), tau.data_ptr(),
+        dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), AP_BF16, B, H, Lq, Lk, D,
+        _strides3(Q), _strides3(K), _strides3(V), _strides3(dO),
+        layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
+        layout_t.col_ptr.data_ptr(), layout_t.row_idx.data_ptr(), layout_t.tile_idx.data_ptr(),
+        layout.block_m, layout.block_n, ctypes.byref(cs), ctypes.byref(ccs), int(bool(causal)),
+        float(softmax_scale), ws.data_ptr(), ws_bytes, _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_sparse_attn_entmax15_bwd")
     return dQ, dK, dV
 
 

@@ -254,8 +254,15 @@ static ap_status bwd_common(const void* Q, const void* K, const void* V, const v
                              const uint64_t* bitmaps, const int32_t* col_ptr,
                              const int32_t* row_idx, const int32_t* tile_idx, int block_m,
                              int block_n, const ap_schedule* sched, const ap_schedule* col_sched, int causal,
-                             float softmax_scale, void* workspace, size_t workspace_bytes, void* stream)
+                             float softmax_scale, void* workspace, size_t workspace_bytes, void* stream,
+                             bool entmax = false)
 {
+    // 1.5-entmax: `lse` carries tau, there is no O (its role is taken by a pass over the entries),
+    // and both schedules are required
+    if (entmax) {
+        if (O || !sched || !col_sched) return AP_ERR_INVALID_ARG;
+        O = dO;                                              // keeps the shared checks below simple
+    }
     if (!Q || !K || !V || !O || !dO || !lse || !dQ || !dK || !dV || !stride_q || !stride_k ||
         !stride_v || !stride_o || !row_ptr || !col_idx || !bitmaps || !col_ptr || !row_idx ||
         !tile_idx || !workspace)
@@ -312,6 +319,11 @@ static ap_status bwd_common(const void* Q, const void* K, const void* V, const v
                     : ap::Schedule{nullptr, nullptr, nullptr, nullptr};
     a.csched = col_sched ? ap::Schedule{col_sched->cnt, col_sched->start, col_sched->cols, col_sched->bitmaps}
                          : ap::Schedule{nullptr, nullptr, nullptr, nullptr};
+    a.entmax = entmax ? 1 : 0;
+    if (entmax) {
+        a.O = nullptr;
+        return ap::launch_bwd_sched(a, true, true, (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
+    }
     return ap::launch_bwd(a, (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
 }
 
@@ -346,6 +358,30 @@ ap_status ap_sparse_attn_bwd_sched(const void* Q, const void* K, const void* V, 
     return bwd_common(Q, K, V, O, dO, lse, dQ, dK, dV, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v,
                       stride_o, row_ptr, col_idx, bitmaps, col_ptr, row_idx, tile_idx, block_m, block_n,
                       sched, col_sched, causal, softmax_scale, workspace, workspace_bytes, stream);
+}
+
+size_t ap_entmax15_bwd_workspace_bytes(int B, int H, int Lq)
+{
+    if (B <= 0 || H <= 0 || Lq <= 0) return 0;
+    return (size_t)B * (size_t)H * (size_t)Lq * sizeof(float);
+}
+
+ap_status ap_sparse_attn_entmax15_bwd(const void* Q, const void* K, const void* V, const void* dO,
+                                      const float* tau, void* dQ, void* dK, void* dV, ap_dtype dtype,
+                                      int B, int H, int Lq, int Lk, int D, const int64_t* stride_q,
+                                      const int64_t* stride_k, const int64_t* stride_v,
+                                      const int64_t* stride_o, const int32_t* row_ptr,
+                                      const int32_t* col_idx, const uint64_t* bitmaps,
+                                      const int32_t* col_ptr, const int32_t* row_idx,
+                                      const int32_t* tile_idx, int block_m, int block_n,
+                                      const ap_schedule* sched, const ap_schedule* col_sched, int causal,
+                                      float softmax_scale, void* workspace, size_t workspace_bytes,
+                                      void* stream)
+{
+    return bwd_common(Q, K, V, nullptr, dO, tau, dQ, dK, dV, dtype, B, H, Lq, Lk, D, stride_q, stride_k,
+                      stride_v, stride_o, row_ptr, col_idx, bitmaps, col_ptr, row_idx, tile_idx, block_m,
+                      block_n, sched, col_sched, causal, softmax_scale, workspace, workspace_bytes, stream,
+                      true);
 }
 
 ap_status ap_build_col_schedule(const int32_t* col_ptr, const int32_t* row_idx, const int32_t* tile_idx,

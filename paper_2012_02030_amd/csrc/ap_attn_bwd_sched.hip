@@ -21,10 +21,18 @@ namespace {
 
 using namespace mfma;
 
+// What the kernels compute per entry.  SOFTMAX: P = exp(s - lse), dS = P (dP - delta) with the
+// per-query statistics lse and delta = <dO, O>.  ENTMAX15 (the 1.5-entmax normaliser of Section 6):
+// u = [s / 2 - tau]_+, P = u^2, dS = u (dP - gbar) with the per-query statistics tau (from the
+// forward pass) and gbar = sum_j u_j dP_j / sum_j u_j, which GBAR, a dQ-shaped pass that stops
+// before the last product, computes first.  For the two entmax modes BwdArgs::lse holds tau and
+// BwdArgs::delta holds gbar.
+enum { SOFTMAX = 0, ENTMAX15 = 1, GBAR = 2 };
+
 __device__ __forceinline__ float lse2_of(float lse) { return lse == -INFINITY ? INFINITY : lse * kLog2e; }
 
-template <int D>
-__global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB)
+template <int D, int MODE>
+__global__ __launch_bounds__(128, D == 128 ? 1 : 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB)
 {
     constexpr int TILE = kBN * D;
     constexpr int KSTEPS = D / 16;
@@ -75,9 +83,11 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB
         }
     }
     const size_t stat = ((size_t)b * a.H + h) * a.Lq + qload;
-    float lse2 = row_ok ? lse2_of(a.lse[stat]) : INFINITY;
-    float delta = row_ok ? a.delta[stat] : 0.f;
-    const float sc = a.scale * kLog2e;
+    // SOFTMAX: base-2 log-sum-exp and delta; entmax modes: tau (+inf for a query without keys) and gbar
+    float lse2 = row_ok ? (MODE == SOFTMAX ? lse2_of(a.lse[stat]) : a.lse[stat]) : INFINITY;
+    float delta = row_ok && MODE != GBAR ? a.delta[stat] : 0.f;
+    const float sc = MODE == SOFTMAX ? a.scale * kLog2e : a.scale * 0.5f;
+    float num = 0.f, den = 0.f;                              // GBAR: this lane's share of sum u dP and sum u
     const int k_swz = hh ^ swz_u<D>(n);
     const TrReadU<D> tr = make_tr_read_u<D>(lane);
 
@@ -155,19 +165,35 @@ __global__ __launch_bounds__(128, 2) void bwd_dq_sched_kernel(BwdArgs a, int nQB
                     const int pos = 8 * (i / 4) + (i % 4);
                     const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)wbits[kb], pos, 1);
                     const float x = fmaf(sacc[kb][i], sc, -lse2);
-                    const float p = __builtin_amdgcn_exp2f(__uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep)));
-                    sacc[kb][i] = p * (pacc[kb][i] - delta); // dS^T
+                    if (MODE == SOFTMAX) {
+                        const float p = __builtin_amdgcn_exp2f(__uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep)));
+                        sacc[kb][i] = p * (pacc[kb][i] - delta);   // dS^T
+                    } else {
+                        const float u = fmaxf(__uint_as_float(__float_as_uint(x) & keep), 0.f);   // pruned: 0
+                        if (MODE == GBAR) {
+                            num = fmaf(u, pacc[kb][i], num);
+                            den += u;
+                        } else {
+                            sacc[kb][i] = u * (pacc[kb][i] - delta);   // dS^T
+                        }
+                    }
                 }
-            tr_mm_64_u<D>(lds + stage * STAGE, sacc, dqacc, tr);   // dQ^T += K^T dS^T
+            if (MODE != GBAR) tr_mm_64_u<D>(lds + stage * STAGE, sacc, dqacc, tr);   // dQ^T += K^T dS^T
         }
         stage ^= 1;
+    }
+    if (MODE == GBAR) {                                      // the two half-wavefronts hold different keys
+        num += __shfl_xor(num, 32, 64);
+        den += __shfl_xor(den, 32, 64);
+        if (row_ok && hh == 0) a.delta[stat] = den > 0.f ? num / den : 0.f;
+        return;
     }
     __syncthreads();                                         // all wavefronts are done with the tiles
     store_rows_bf16<D>(smem + wave * 32 * D, dqacc, a.scale, lane,
                        dQp + (size_t)(qb * 64 + wave * 32) * a.sq[2], a.sq[2], a.Lq - (qb * 64 + wave * 32));
 }
 
-template <int D>
+template <int D, int NORM>
 __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nKB)
 {
     constexpr int TILE = kBN * D;
@@ -261,7 +287,7 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
             vreg[kk] = *reinterpret_cast<const bf16x8*>(vr + 16 * kk);
         }
     }
-    const float sc = a.scale * kLog2e;
+    const float sc = NORM == SOFTMAX ? a.scale * kLog2e : a.scale * 0.5f;
     const int k_swz = hh ^ swz_u<D>(n);
     const TrReadU<D> tr = make_tr_read_u<D>(lane);
 
@@ -298,7 +324,7 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
             const int q = m.start >= 0 ? m.start + tid : m.row;   // (all lanes hold the same start)
             const int ql = q < a.Lq ? q : a.Lq - 1;
             const float l = a.lse[stat_base + ql], d = a.delta[stat_base + ql];
-            s.lse = q < a.Lq ? l : -INFINITY;
+            s.lse = q < a.Lq ? l : (NORM == SOFTMAX ? -INFINITY : INFINITY);   // lse, or tau
             s.delta = q < a.Lq ? d : 0.f;
             s.word = a.csched.bitmaps[(size_t)t * 64 + tid];
         }
@@ -320,7 +346,7 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
 
     Meta cur, nxt;
     Stat st;
-    st.lse = -INFINITY;
+    st.lse = NORM == SOFTMAX ? -INFINITY : INFINITY;
     st.delta = 0.f;
     st.word = 0;
     if (t0 < t1) {
@@ -338,7 +364,7 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
     for (int t = t0; t < t1; ++t) {
         wait_vmem();                                         // entry t, its statistics and the metadata of t + 1
         if (tid < 64) {
-            s_lse2[stage][tid] = lse2_of(st.lse);
+            s_lse2[stage][tid] = NORM == SOFTMAX ? lse2_of(st.lse) : st.lse;
             s_delta[stage][tid] = st.delta;
             s_half[stage][0][tid] = (uint32_t)st.word;
             s_half[stage][1][tid] = (uint32_t)(st.word >> 32);
@@ -370,9 +396,15 @@ __global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nK
                     // pruned entries: the exponent's argument is replaced by -inf with a bit-select
                     const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe((int)we[e], n, 1);
                     const float x = fmaf(sacc[qblk][i], sc, -le[e]);
-                    const float p = __builtin_amdgcn_exp2f(__uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep)));
-                    sacc[qblk][i] = p;                       // P
-                    pacc[qblk][i] = p * (pacc[qblk][i] - de[e]);   // dS
+                    if (NORM == SOFTMAX) {
+                        const float p = __builtin_amdgcn_exp2f(__uint_as_float((__float_as_uint(x) & keep) | (0xff800000u & ~keep)));
+                        sacc[qblk][i] = p;                   // P
+                        pacc[qblk][i] = p * (pacc[qblk][i] - de[e]);   // dS
+                    } else {
+                        const float u = fmaxf(__uint_as_float(__float_as_uint(x) & keep), 0.f);   // pruned: 0
+                        sacc[qblk][i] = u * u;               // P
+                        pacc[qblk][i] = u * (pacc[qblk][i] - de[e]);   // dS
+                    }
                 }
             }
         tr_mm_64_u<D>(lds + stage * STAGE + TILE, sacc, dvacc, tr);   // dV^T += dO^T P
@@ -391,13 +423,23 @@ template <int D>
 hipError_t launch_d(const BwdArgs& a, bool dq, bool dkv, hipStream_t stream)
 {
     const int nQB = (a.Lq + 63) / 64, nKB = (a.Lk + 63) / 64;
+    const dim3 qgrid((unsigned)(a.B * a.H * nQB)), kgrid((unsigned)(a.B * a.H * nKB));
+    if (a.entmax) {                                          // gbar first, then the two gradient kernels
+        hipLaunchKernelGGL((bwd_dq_sched_kernel<D, GBAR>), qgrid, dim3(128), 0, stream, a, nQB);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_dq_sched_kernel<D, ENTMAX15>), qgrid, dim3(128), 0, stream, a, nQB);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_dkv_sched_kernel<D, ENTMAX15>), kgrid, dim3(128), 0, stream, a, nKB);
+        return hipGetLastError();
+    }
     if (dq) {
-        hipLaunchKernelGGL(bwd_dq_sched_kernel<D>, dim3((unsigned)(a.B * a.H * nQB)), dim3(128), 0, stream, a, nQB);
+        hipLaunchKernelGGL((bwd_dq_sched_kernel<D, SOFTMAX>), qgrid, dim3(128), 0, stream, a, nQB);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (dkv)
-        hipLaunchKernelGGL(bwd_dkv_sched_kernel<D>, dim3((unsigned)(a.B * a.H * nKB)), dim3(128), 0, stream, a, nKB);
+    if (dkv) hipLaunchKernelGGL((bwd_dkv_sched_kernel<D, SOFTMAX>), kgrid, dim3(128), 0, stream, a, nKB);
     return hipGetLastError();
 }
 

@@ -85,9 +85,11 @@ struct BwdArgs {
     float* delta;                   // [B, H, Lq] scratch: sum_d dO * O of each row
     Schedule sched;                 // row schedule for dQ; all null: walk the layout
     Schedule csched;                // column schedule for dK, dV; all null: walk the transposed layout
+    int entmax;                     // 1: 1.5-entmax (both schedules required; lse holds tau, delta gets gbar)
 };
 hipError_t launch_bwd(const BwdArgs& a, hipStream_t stream);
-// the kernels that walk schedules (ap_attn_bwd_sched.hip); delta must have been computed
+// the kernels that walk schedules (ap_attn_bwd_sched.hip); softmax: delta must have been computed;
+// entmax: runs the gbar pass and both gradient kernels whatever dq and dkv say
 hipError_t launch_bwd_sched(const BwdArgs& a, bool dq, bool dkv, hipStream_t stream);
 // column schedule (ap_col_schedule.hip): entry e of block column c is element col_ptr[c] + e
 hipError_t launch_build_col_schedule(const int32_t* col_ptr, const int32_t* row_idx, const int32_t* tile_idx,

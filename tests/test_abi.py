@@ -306,6 +306,35 @@ def test_scheduled_backward_arguments(L):
     assert build(tile_idx=fake + 2) == ap.AP_ERR_INVALID_ARG
 
 
+def test_entmax_backward_arguments(L):
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+    assert ap.ap_entmax15_bwd_workspace_bytes(4, 16, 4096) == 4 * 16 * 4096 * 4
+    assert ap.ap_entmax15_bwd_workspace_bytes(0, 16, 4096) == 0
+    ws = ap.ap_entmax15_bwd_workspace_bytes(1, 2, 64)
+    good = ap._CSchedule(fake, fake, fake, fake)
+
+    def bwd(sched=good, col_sched=good, **over):
+        a = dict(dtype=ap.AP_BF16, D=64, bm=64, tau=fake + 0x900000, ws_bytes=ws, dQ=fake + 0x500000)
+        a.update(over)
+        ptrs = [fake + i * 0x100000 for i in range(4)]
+        return L.ap_sparse_attn_entmax15_bwd(*ptrs, a["tau"], a["dQ"], fake + 0x600000, fake + 0x700000,
+                                             a["dtype"], 1, 2, 64, 64, a["D"], s, s, s, s, fake, fake, fake, fake,
+                                             fake, fake, a["bm"], 64,
+                                             ctypes.byref(sched) if sched else None,
+                                             ctypes.byref(col_sched) if col_sched else None, 0, 0.0,
+                                             fake, a["ws_bytes"], None)
+
+    assert bwd(sched=None) == ap.AP_ERR_INVALID_ARG                            # both schedules are required
+    assert bwd(col_sched=None) == ap.AP_ERR_INVALID_ARG
+    assert bwd(tau=None) == ap.AP_ERR_INVALID_ARG
+    assert bwd(dQ=fake) == ap.AP_ERR_INVALID_ARG                               # dQ aliases Q
+    assert bwd(dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    assert bwd(D=48) == ap.AP_ERR_UNSUPPORTED
+    assert bwd(bm=128) == ap.AP_ERR_UNSUPPORTED
+    assert bwd(ws_bytes=ws - 1) == ap.AP_ERR_CAPACITY
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ap, "_lib", None)
     monkeypatch.setattr(ap, "LIB_PATH", "/nonexistent/libap_mi355x.so")
