@@ -98,6 +98,18 @@ ap_status ap_build_layout(const uint8_t *mask, int H, int Lq, int Lk, int block_
                           int32_t *row_ptr, int32_t *col_idx, uint64_t *bitmaps, int64_t cap,
                           int64_t *nnz_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The same for the top-left Lq x Lk corner of a stored mask [H, Lq_stored, Lk_stored] (Section 6:
+ * sequence lengths vary across a data set while the mask of a layer and head is fixed, so a
+ * shorter sequence uses the corner of the mask that covers it).  The result is the layout that
+ * ap_build_layout would produce for a contiguous copy of that corner; nothing is copied.
+ * Lq <= Lq_stored, Lk <= Lk_stored; workspace as for (H, Lq, Lk).
+ */
+ap_status ap_build_layout_cropped(const uint8_t *mask, int H, int Lq_stored, int Lk_stored, int Lq,
+                                  int Lk, int block_m, int block_n, int32_t *row_ptr, int32_t *col_idx,
+                                  uint64_t *bitmaps, int64_t cap, int64_t *nnz_out, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Visit schedule: an optional, derived re-packing of a layout for the attention kernel.
  *

@@ -25,7 +25,7 @@ AP_F32 = 0
 AP_BF16 = 1
 
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
-           "ap_build_layout", "ap_build_schedule", "ap_sparse_attn_fwd",
+           "ap_build_layout", "ap_build_layout_cropped", "ap_build_schedule", "ap_sparse_attn_fwd",
            "ap_sparse_attn_entmax15_fwd", "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
            "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
            "ap_build_col_schedule", "ap_sparse_attn_bwd_sched",
@@ -68,6 +68,9 @@ def lib() -> ctypes.CDLL:
         L.ap_build_layout.restype = i32
         L.ap_build_layout.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp,
                                       ctypes.c_size_t, vp]
+        L.ap_build_layout_cropped.restype = i32
+        L.ap_build_layout_cropped.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp,
+                                              ctypes.c_size_t, vp]
         L.ap_build_schedule.restype = i32
         L.ap_build_schedule.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i64, i32, i32,
                                         ctypes.POINTER(_CSchedule), vp]
@@ -159,14 +162,17 @@ def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
 
 def ap_build_layout(mask: torch.Tensor, block_m: int = 64, block_n: int = 64,
                     cap: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None,
-                    count_only: bool = False) -> Layout:
-    """mask: uint8/bool device tensor [H, Lq, Lk], nonzero = kept.  Asynchronous on the stream."""
+                    count_only: bool = False, crop: Optional[tuple] = None) -> Layout:
+    """mask: uint8/bool device tensor [H, Lq, Lk], nonzero = kept.  Asynchronous on the stream.
+
+    crop = (Lq', Lk') builds the layout of the mask's top-left corner (ap_build_layout_cropped)."""
     if mask.dtype == torch.bool:
         mask = mask.view(torch.uint8)
     if mask.dtype != torch.uint8 or mask.dim() != 3 or not mask.is_cuda:
         raise ValueError("mask must be a uint8/bool device tensor [H, Lq, Lk]")
     mask = mask.contiguous()
-    H, Lq, Lk = mask.shape
+    H, Lq_stored, Lk_stored = mask.shape
+    Lq, Lk = (Lq_stored, Lk_stored) if crop is None else (int(crop[0]), int(crop[1]))
     max_tiles = ap_layout_max_tiles(H, Lq, Lk, block_m, block_n)
     if max_tiles < 0:
         raise ApError(AP_ERR_UNSUPPORTED, "ap_layout_max_tiles")
@@ -187,9 +193,14 @@ def ap_build_layout(mask: torch.Tensor, block_m: int = 64, block_n: int = 64,
         col_idx = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
         bitmaps = torch.empty((max(cap, 1), block_m, W), dtype=torch.int64, device=dev)
         cptr, bptr = col_idx.data_ptr(), bitmaps.data_ptr()
-    st = lib().ap_build_layout(mask.data_ptr(), H, Lq, Lk, block_m, block_n, row_ptr.data_ptr(),
-                               cptr, bptr, cap, nnz.data_ptr(), ws.data_ptr(), ws_bytes,
-                               _stream_ptr(stream))
+    if crop is None:
+        st = lib().ap_build_layout(mask.data_ptr(), H, Lq, Lk, block_m, block_n, row_ptr.data_ptr(),
+                                   cptr, bptr, cap, nnz.data_ptr(), ws.data_ptr(), ws_bytes,
+                                   _stream_ptr(stream))
+    else:
+        st = lib().ap_build_layout_cropped(mask.data_ptr(), H, Lq_stored, Lk_stored, Lq, Lk, block_m, block_n,
+                                           row_ptr.data_ptr(), cptr, bptr, cap, nnz.data_ptr(),
+                                           ws.data_ptr(), ws_bytes, _stream_ptr(stream))
     if st != AP_OK:
         raise ApError(st, "ap_build_layout")
     # ws is released to torch's caching allocator here; the allocator is stream-ordered, so the

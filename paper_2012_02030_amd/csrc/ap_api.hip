@@ -49,9 +49,10 @@ size_t ap_layout_workspace_bytes(int H, int Lq, int Lk, int block_m, int block_n
     return total;
 }
 
-ap_status ap_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int block_m, int block_n,
-                          int32_t* row_ptr, int32_t* col_idx, uint64_t* bitmaps, int64_t cap,
-                          int64_t* nnz_out, void* workspace, size_t workspace_bytes, void* stream)
+static ap_status build_layout_common(const uint8_t* mask, long long stride_h, long long stride_row, int H,
+                                     int Lq, int Lk, int block_m, int block_n, int32_t* row_ptr,
+                                     int32_t* col_idx, uint64_t* bitmaps, int64_t cap, int64_t* nnz_out,
+                                     void* workspace, size_t workspace_bytes, void* stream)
 {
     if (H <= 0 || Lq <= 0 || Lk <= 0 || block_m <= 0 || block_n <= 0) return AP_ERR_INVALID_ARG;
     if (!ap::layout_shape_ok(H, Lq, Lk, block_m, block_n)) return AP_ERR_UNSUPPORTED;
@@ -63,10 +64,28 @@ ap_status ap_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int block_
         return AP_ERR_INVALID_ARG;
     if (workspace_bytes < ap_layout_workspace_bytes(H, Lq, Lk, block_m, block_n)) return AP_ERR_CAPACITY;
 
-    const hipError_t e = ap::launch_build_layout(mask, H, Lq, Lk, block_m, block_n, row_ptr, col_idx,
-                                                 bitmaps, (long long)cap, nnz_out, workspace,
-                                                 (hipStream_t)stream);
+    const hipError_t e = ap::launch_build_layout(mask, stride_h, stride_row, H, Lq, Lk, block_m, block_n,
+                                                 row_ptr, col_idx, bitmaps, (long long)cap, nnz_out,
+                                                 workspace, (hipStream_t)stream);
     return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+ap_status ap_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int block_m, int block_n,
+                          int32_t* row_ptr, int32_t* col_idx, uint64_t* bitmaps, int64_t cap,
+                          int64_t* nnz_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return build_layout_common(mask, (long long)Lq * Lk, Lk, H, Lq, Lk, block_m, block_n, row_ptr, col_idx,
+                               bitmaps, cap, nnz_out, workspace, workspace_bytes, stream);
+}
+
+ap_status ap_build_layout_cropped(const uint8_t* mask, int H, int Lq_stored, int Lk_stored, int Lq, int Lk,
+                                  int block_m, int block_n, int32_t* row_ptr, int32_t* col_idx,
+                                  uint64_t* bitmaps, int64_t cap, int64_t* nnz_out, void* workspace,
+                                  size_t workspace_bytes, void* stream)
+{
+    if (Lq_stored <= 0 || Lk_stored <= 0 || Lq > Lq_stored || Lk > Lk_stored) return AP_ERR_INVALID_ARG;
+    return build_layout_common(mask, (long long)Lq_stored * Lk_stored, Lk_stored, H, Lq, Lk, block_m, block_n,
+                               row_ptr, col_idx, bitmaps, cap, nnz_out, workspace, workspace_bytes, stream);
 }
 
 ap_status ap_build_schedule(const int32_t* row_ptr, const int32_t* col_idx, const uint64_t* bitmaps,

@@ -10,9 +10,10 @@ namespace ap {
 bool layout_shape_ok(int H, int Lq, int Lk, int BM, int BN);
 void layout_workspace_plan(int H, int Lq, int Lk, int BM, int BN, size_t* flags_off,
                            size_t* counts_off, size_t* dense_off, size_t* total);
-hipError_t launch_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int BM, int BN,
-                               int32_t* row_ptr, int32_t* col_idx, uint64_t* bitmaps,
-                               long long cap, int64_t* nnz_out, void* workspace,
+// mask[h, i, j] is the byte at h * stride_h + i * stride_row + j
+hipError_t launch_build_layout(const uint8_t* mask, long long stride_h, long long stride_row, int H,
+                               int Lq, int Lk, int BM, int BN, int32_t* row_ptr, int32_t* col_idx,
+                               uint64_t* bitmaps, long long cap, int64_t* nnz_out, void* workspace,
                                hipStream_t stream);
 
 // ---- visit schedule (ap_schedule.hip): entry e of block row r is element row_ptr[r] + e

@@ -31,8 +31,9 @@ __device__ __forceinline__ uint32_t nonzero_bytes_to_bits(uint32_t x)
 // One wavefront per window.  lanes_per_row = BN/16 lanes cover one mask row of the window with
 // one 16-byte load each; 64/lanes_per_row rows are covered per pass.
 __global__ __launch_bounds__(256) void tile_scan_kernel(
-    const uint8_t* __restrict__ mask, int H, int Lq, int Lk, int BM, int BN, int nQB, int nKB,
-    int vec_ok, uint8_t* __restrict__ flags, uint64_t* __restrict__ dense /* may be null */)
+    const uint8_t* __restrict__ mask, long long stride_h, long long stride_row, int H, int Lq, int Lk,
+    int BM, int BN, int nQB, int nKB, int vec_ok, uint8_t* __restrict__ flags,
+    uint64_t* __restrict__ dense /* may be null */)
 {
     const int lane = threadIdx.x & 63;
     const long long tile = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -55,8 +56,8 @@ __global__ __launch_bounds__(256) void tile_scan_kernel(
         const int i = qb * BM + rr;
         uint32_t bits = 0;
         if (rr < BM && i < Lq && j0 < Lk) {
-            const uint8_t* p = mask + ((size_t)h * Lq + i) * (size_t)Lk + j0;
-            if (vec_ok) {                              // Lk % 16 == 0: the 16 bytes are in range and aligned
+            const uint8_t* p = mask + (size_t)h * stride_h + (size_t)i * stride_row + j0;
+            if (vec_ok) {                              // Lk and the row pitch % 16 == 0: the 16 bytes are in range and aligned
                 const uint4 v = *reinterpret_cast<const uint4*>(p);
                 bits = nonzero_bytes_to_bits(v.x) | (nonzero_bytes_to_bits(v.y) << 4) |
                        (nonzero_bytes_to_bits(v.z) << 8) | (nonzero_bytes_to_bits(v.w) << 12);
@@ -178,8 +179,8 @@ void layout_workspace_plan(int H, int Lq, int Lk, int BM, int BN, size_t* flags_
     *total = off;
 }
 
-hipError_t launch_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int BM, int BN,
-                               int32_t* row_ptr, int32_t* col_idx, uint64_t* bitmaps,
+hipError_t launch_build_layout(const uint8_t* mask, long long stride_h, long long stride_row, int H,
+                               int Lq, int Lk, int BM, int BN, int32_t* row_ptr, int32_t* col_idx, uint64_t* bitmaps,
                                long long cap, int64_t* nnz_out, void* workspace,
                                hipStream_t stream)
 {
@@ -191,14 +192,15 @@ hipError_t launch_build_layout(const uint8_t* mask, int H, int Lq, int Lk, int B
     uint8_t* flags = (uint8_t*)workspace + flags_off;
     int32_t* counts = (int32_t*)((uint8_t*)workspace + counts_off);
     uint64_t* dense = col_idx ? (uint64_t*)((uint8_t*)workspace + dense_off) : nullptr;
-    const int vec_ok = (Lk % 16 == 0) && (((uintptr_t)mask & 15) == 0);
+    const int vec_ok = (Lk % 16 == 0) && (stride_row % 16 == 0) && (stride_h % 16 == 0) &&
+                       (((uintptr_t)mask & 15) == 0);
 
     const int waves_per_block = 4;
     const unsigned tile_blocks = (unsigned)((n_tiles + waves_per_block - 1) / waves_per_block);
     const unsigned row_blocks = (unsigned)((n_rows + waves_per_block - 1) / waves_per_block);
 
     hipLaunchKernelGGL(tile_scan_kernel, dim3(tile_blocks), dim3(64 * waves_per_block), 0, stream,
-                       mask, H, Lq, Lk, BM, BN, nQB, nKB, vec_ok, flags, dense);
+                       mask, stride_h, stride_row, H, Lq, Lk, BM, BN, nQB, nKB, vec_ok, flags, dense);
     hipLaunchKernelGGL(row_count_kernel, dim3(row_blocks), dim3(64 * waves_per_block), 0, stream,
                        flags, n_rows, nKB, counts);
     hipLaunchKernelGGL(row_scan_kernel, dim3(1), dim3(1024), 0, stream, counts, n_rows, row_ptr,

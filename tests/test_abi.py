@@ -335,6 +335,22 @@ def test_entmax_backward_arguments(L):
     assert bwd(ws_bytes=ws - 1) == ap.AP_ERR_CAPACITY
 
 
+def test_cropped_layout_arguments(L):
+    fake = 0x1000
+    ws = ap.ap_layout_workspace_bytes(2, 64, 64, 64, 64)
+
+    def crop(LqS=128, LkS=128, Lq=64, Lk=64, mask=fake, ws_bytes=ws):
+        return L.ap_build_layout_cropped(mask, 2, LqS, LkS, Lq, Lk, 64, 64, fake, fake, fake, 8, None, fake,
+                                         ws_bytes, None)
+
+    assert crop(Lq=129) == ap.AP_ERR_INVALID_ARG            # the corner must lie inside the stored mask
+    assert crop(Lk=200) == ap.AP_ERR_INVALID_ARG
+    assert crop(LqS=0) == ap.AP_ERR_INVALID_ARG
+    assert crop(Lq=0) == ap.AP_ERR_INVALID_ARG
+    assert crop(mask=None) == ap.AP_ERR_INVALID_ARG
+    assert crop(ws_bytes=ws - 1) == ap.AP_ERR_CAPACITY
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ap, "_lib", None)
     monkeypatch.setattr(ap, "LIB_PATH", "/nonexistent/libap_mi355x.so")

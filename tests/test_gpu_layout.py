@@ -78,3 +78,44 @@ def test_full_size_long_context_mask():
     mask = synth.make_mask(cfg)
     lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
     assert_layout_equal(lay, mask)
+
+
+@pytest.mark.parametrize("stored,crop,bm,bn", [
+    ((3, 300, 512), (300, 512), 64, 64),     # the whole mask
+    ((3, 300, 512), (130, 256), 64, 64),     # vector path: pitch and cropped width multiples of 16
+    ((3, 300, 512), (257, 201), 64, 64),     # byte path: the cropped width ends inside a 16-byte group
+    ((2, 200, 333), (64, 70), 64, 64),       # pitch not a multiple of 16
+    ((2, 200, 333), (1, 1), 64, 64),
+    ((2, 260, 260), (129, 129), 128, 64),
+    ((2, 100, 160), (33, 48), 16, 16),
+])
+def test_cropped_layout_is_the_layout_of_the_corner(stored, crop, bm, bn):
+    """One stored mask serves every shorter sequence through its top-left corner; kept entries
+    right of and below the corner must not leak in."""
+    H, LqS, LkS = stored
+    mask = synth.random_mask(H, LqS, LkS, 0.05, seed=LqS + LkS + crop[0])
+    mask[:, :, LkS - 1] = 1
+    mask[:, LqS - 1, :] = 1
+    lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), bm, bn, crop=crop)
+    assert (lay.Lq, lay.Lk) == crop
+    assert_layout_equal(lay, np.ascontiguousarray(mask[:, :crop[0], :crop[1]]))
+
+
+def test_attention_under_a_cropped_mask():
+    from gpu_util import to_device, TOL
+    H, LqS, LkS, D = 2, 256, 320, 64
+    Lq, Lk = 150, 201
+    mask = synth.random_mask(H, LqS, LkS, 0.2, seed=9)
+    rng = np.random.default_rng(10)
+    Q, K, V = (rng.standard_normal(s, dtype=np.float32) for s in ((2, H, Lq, D), (2, H, Lk, D), (2, H, Lk, D)))
+    lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64, crop=(Lq, Lk))
+    sched = ap.ap_build_schedule(lay, causal=False)
+    dq, rq = to_device(Q, "bf16")
+    dk, rk = to_device(K, "bf16")
+    dv, rv = to_device(V, "bf16")
+    O, lse = ap.ap_sparse_attn_fwd(dq, dk, dv, lay, sched=sched)
+    torch.cuda.synchronize()
+    O_ref, lse_ref = oracle.masked_attention(rq, rk, rv, mask[:, :Lq, :Lk])
+    assert np.abs(O.double().cpu().numpy() - O_ref).max() <= TOL["bf16"]
+    ok = ~np.isneginf(lse_ref)
+    assert np.abs(lse.double().cpu().numpy()[ok] - lse_ref[ok]).max() <= TOL["bf16"]
