@@ -196,3 +196,40 @@ def test_scheduled_backward_full_size_c5_two_slices_against_oracle():
             err = float(np.abs(sl(got) - want).max())
             tol = 2e-2 * max(1.0, float(np.abs(want).max()))
             assert err <= tol, "%s[%d,%d]: %.3e > %.3e" % (name, b, h, err, tol)
+
+
+def nan_padded(t, extra=64):
+    """The same values as t [B, H, L, D], stored with `extra` rows of NaN behind every head's last row."""
+    B, H, L, D = t.shape
+    store = torch.full((B, H, L + extra, D), float("nan"), dtype=t.dtype, device=t.device)
+    store[:, :, :L] = t
+    return store[:, :, :L]
+
+
+@pytest.mark.parametrize("use_sched", [False, True])
+def test_rows_behind_the_last_row_are_never_used(use_sched):
+    """Ragged last tiles: whatever is stored behind row L - 1 of Q, K, V, O, dO must not reach a gradient."""
+    B, H, Lq, Lk, D = 2, 2, 130, 150, 128
+    Q, K, V, dO = rand_inputs(41, B, H, Lq, Lk, D)
+    mask = synth.random_mask(H, Lq, Lk, 0.4, seed=42)
+    mask[:, :, Lk - 1] = 1
+    mask[:, Lq - 1, :] = 1
+    dq, rq = to_device(Q, "bf16")
+    dk, rk = to_device(K, "bf16")
+    dv, rv = to_device(V, "bf16")
+    dg, rg = to_device(dO, "bf16")
+    lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
+    lt = ap.ap_build_layout_transpose(lay)
+    kw = {}
+    if use_sched:
+        kw = dict(sched=ap.ap_build_schedule(lay, causal=False), col_sched=ap.ap_build_col_schedule(lay, lt, causal=False))
+    pq, pk, pv, pg = nan_padded(dq), nan_padded(dk), nan_padded(dv), nan_padded(dg)
+    O, lse = ap.ap_sparse_attn_fwd(pq, pk, pv, lay)
+    pO = nan_padded(O)
+    got3 = ap.ap_sparse_attn_bwd(pq, pk, pv, pO, pg, lse, lay, lt, **kw)
+    torch.cuda.synchronize()
+    ref = oracle.masked_attention_backward(rq, rk, rv, mask, rg)
+    for name, got, want in zip(("dQ", "dK", "dV"), got3, ref):
+        g = got.double().cpu().numpy()
+        assert np.isfinite(g).all(), name + " picked up padding"
+        assert float(np.abs(g - want).max()) <= 2e-2 * max(1.0, float(np.abs(want).max()))
