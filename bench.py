@@ -488,6 +488,48 @@ def main():
             "hbm_roofline_frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         }
 
+    def run_decode(cfg, steps):
+        """One new query per (example, head) against cfg's long key sequence (cfg's last mask row):
+        the one-workgroup-per-query call next to the tiled calls on the same layout."""
+        mask_np = np.ascontiguousarray(synth.make_mask(cfg)[:, -1:, :])
+        lay = ap.ap_build_layout(torch.from_numpy(mask_np).to(dev), 64, 64)
+        sched = ap.ap_build_schedule(lay, causal=cfg.causal, min_cols=args.min_cols)
+        Q, K, V = synth.make_qkv(cfg)
+        q, k, v = (torch.from_numpy(x).to(torch.bfloat16).to(dev) for x in (Q[:, :, -1:, :], K, V))
+        q = q.contiguous()
+        out = torch.empty_like(q)
+
+        def timed(fn, n):
+            fn()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            torch.cuda.synchronize()
+            evs[0].record()
+            for i in range(n):
+                fn()
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            return float(np.mean([evs[i].elapsed_time(evs[i + 1]) for i in range(n)]))
+
+        dec_table = {str(sp): timed(lambda: ap.ap_sparse_attn_decode(q, k, v, lay, causal=cfg.causal, out=out,
+                                                                     splits=sp), steps) for sp in (1, 4, 8, 16)}
+        dec_ms = min(dec_table.values())
+        plain_ms = timed(lambda: ap.ap_sparse_attn_fwd(q, k, v, lay, causal=cfg.causal, out=out, sched=sched), steps)
+        split_ms = min(timed(lambda: ap.ap_sparse_attn_fwd_split(q, k, v, lay, sp, causal=cfg.causal, out=out,
+                                                                 sched=sched), steps) for sp in (8, 16, 32))
+        kept = int(mask_np.sum())
+        alg = 2 * cfg.B * (2 * kept * cfg.D + 2 * cfg.H * cfg.D)          # kept keys' K and V rows, Q and O
+        return {
+            "shape": {"B": cfg.B, "H": cfg.H, "Lq": 1, "Lk": cfg.Lk, "D": cfg.D, "causal": cfg.causal},
+            "kept_keys_per_layer": kept,
+            "decode_call_ms": dec_ms,
+            "decode_call_ms_by_splits": dec_table,
+            "tiled_call_ms": plain_ms,
+            "tiled_split_call_ms": split_ms,
+            "hbm_alg_bytes": alg,
+            "hbm_gbs": alg / (dec_ms * 1e-3) / 1e9,
+            "hbm_roofline_frac": alg / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        }
+
     def run_entmax(cfg, mask_np, steps):
         """1.5-entmax forward of cfg under its AP mask (plain layout walk) next to the softmax
         forward over the same layout walk."""
@@ -550,7 +592,8 @@ def main():
         return
 
     if args.only_split:
-        print(json.dumps({"split_forward": run_split_forward(synth.EXTRA_CONFIGS["X1"], args.steps)}), flush=True)
+        print(json.dumps({"split_forward": run_split_forward(synth.EXTRA_CONFIGS["X1"], args.steps),
+                          "decode": run_decode(synth.EXTRA_CONFIGS["X1"], args.steps)}), flush=True)
         return
 
     if args.only_backward:
@@ -630,9 +673,11 @@ def main():
         torch.cuda.empty_cache()
 
     split_forward = None
+    decode = None
     if not args.only:
         log("timing the split forward call on the long-memory shape X1 ...")
         split_forward = run_split_forward(synth.EXTRA_CONFIGS["X1"], 20)
+        decode = run_decode(synth.EXTRA_CONFIGS["X1"], 20)
         torch.cuda.empty_cache()
 
     entmax = None
@@ -685,6 +730,7 @@ def main():
         "mask_construction": mask_construction,
         "backward": backward,
         "split_forward": split_forward,
+        "decode": decode,
         "entmax15_forward": entmax,
         "per_config": per_config,
     }

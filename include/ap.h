@@ -216,6 +216,33 @@ ap_status ap_sparse_attn_fwd_split(const void *Q, const void *K, const void *V, 
                                    void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Masked attention forward for one or a few queries against many keys (the limit of the
+ * cached-memory setting of Section 4.1: a new position attends to everything stored before it under
+ * the layer's fixed mask; with `causal` the limit is aligned bottom-right as everywhere else).
+ *
+ * Same arguments as ap_sparse_attn_fwd_split without the schedule, same result up to rounding as
+ * ap_sparse_attn_fwd.  `splits` workgroups per (batch, head, query) read the K and V rows of that
+ * query's kept keys and nothing else; the probabilities stay in fp32 (they are not rounded to bf16
+ * before multiplying V).  Meant for Lq up to a few dozen; correct for any Lq.
+ *
+ *   splits        >= 1, at most 1024; 1 writes O directly and needs no workspace; choose it so
+ *                 that B*H*Lq*splits reaches the number of compute units (256)
+ *   workspace     for splits > 1: device scratch of at least
+ *                 ap_fwd_split_workspace_bytes(B, H, Lq, D, splits) bytes, 16-byte aligned
+ *
+ * Supported: dtype = AP_BF16, D in {32, 64, 128}, block_n = 64, block_m = 64 or 128.
+ * One launch, two with splits > 1.  Deterministic.
+ * ------------------------------------------------------------------------------------------- */
+ap_status ap_sparse_attn_decode(const void *Q, const void *K, const void *V, void *O, float *lse,
+                                ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                const int64_t *stride_q, const int64_t *stride_k,
+                                const int64_t *stride_v, const int64_t *stride_o,
+                                const int32_t *row_ptr, const int32_t *col_idx,
+                                const uint64_t *bitmaps, int block_m, int block_n, int causal,
+                                float softmax_scale, int splits, void *workspace,
+                                size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Masked attention forward with the 1.5-entmax normaliser (Section 6: the experiments are repeated
  * with 1.5-entmax in place of softmax, together with the pruning mask).
  *

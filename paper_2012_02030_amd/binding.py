@@ -27,6 +27,7 @@ AP_BF16 = 1
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
            "ap_build_layout", "ap_build_layout_cropped", "ap_build_schedule", "ap_sparse_attn_fwd",
            "ap_sparse_attn_entmax15_fwd", "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
+           "ap_sparse_attn_decode",
            "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
            "ap_build_col_schedule", "ap_sparse_attn_bwd_sched",
            "ap_entmax15_bwd_workspace_bytes", "ap_sparse_attn_entmax15_bwd",
@@ -80,6 +81,12 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(i64), ctypes.POINTER(i64),
                                          vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
                                          ctypes.c_float, vp]
+        L.ap_sparse_attn_decode.restype = i32
+        L.ap_sparse_attn_decode.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                            ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                            ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                            vp, vp, vp, i32, i32, i32, ctypes.c_float, i32, vp,
+                                            ctypes.c_size_t, vp]
         L.ap_sparse_attn_entmax15_fwd.restype = i32
         L.ap_sparse_attn_entmax15_fwd.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
                                                   ctypes.POINTER(i64), ctypes.POINTER(i64),
@@ -291,6 +298,40 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
         int(bool(causal)), float(softmax_scale), _stream_ptr(stream))
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_fwd")
+    return out, lse
+
+
+def ap_sparse_attn_decode(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout: Layout,
+                          causal: bool = False, softmax_scale: float = 0.0,
+                          out: Optional[torch.Tensor] = None, return_lse: bool = True,
+                          stream: Optional[torch.cuda.Stream] = None, splits: int = 1):
+    """ap_sparse_attn_fwd for one or a few queries against many keys (bf16), `splits` workgroups
+    per query.  Returns (O, lse)."""
+    if Q.dtype != torch.bfloat16 or K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise ValueError("Q, K, V must be bfloat16")
+    B, H, Lq, D = Q.shape
+    Lk = K.shape[2]
+    if tuple(K.shape) != (B, H, Lk, D) or tuple(V.shape) != (B, H, Lk, D):
+        raise ValueError("K/V shape mismatch")
+    if (H, Lq, Lk) != (layout.H, layout.Lq, layout.Lk):
+        raise ValueError("layout was built for other sizes")
+    for t in (Q, K, V):
+        if t.stride(3) != 1:
+            raise ValueError("last dimension must be contiguous")
+    if out is None:
+        out = torch.empty((B, H, Lq, D), dtype=Q.dtype, device=Q.device)
+    lse = torch.empty((B, H, Lq), dtype=torch.float32, device=Q.device) if return_lse else None
+    ws_bytes = ap_fwd_split_workspace_bytes(B, H, Lq, D, splits) if splits > 1 else 0
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=Q.device)
+    st = lib().ap_sparse_attn_decode(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+        lse.data_ptr() if lse is not None else None, AP_BF16, B, H, Lq, Lk, D,
+        _strides3(Q), _strides3(K), _strides3(V), _strides3(out),
+        layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
+        layout.block_m, layout.block_n, int(bool(causal)), float(softmax_scale), int(splits),
+        ws.data_ptr(), ws_bytes, _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_sparse_attn_decode")
     return out, lse
 
 

@@ -123,7 +123,8 @@ static ap_status fwd_common(const void* Q, const void* K, const void* V, void* O
                             const int32_t* row_ptr, const int32_t* col_idx,
                             const uint64_t* bitmaps, int block_m, int block_n,
                             const ap_schedule* sched, int causal, float softmax_scale, int splits,
-                            void* workspace, size_t workspace_bytes, void* stream, bool entmax = false)
+                            void* workspace, size_t workspace_bytes, void* stream, bool entmax = false,
+                            bool decode = false)
 {
     if (!Q || !K || !V || !O || !stride_q || !stride_k || !stride_v || !stride_o || !row_ptr ||
         !col_idx || !bitmaps)
@@ -162,12 +163,15 @@ static ap_status fwd_common(const void* Q, const void* K, const void* V, void* O
         return AP_ERR_UNSUPPORTED;
 
     if (entmax && (dtype != AP_BF16 || block_m != 64)) return AP_ERR_UNSUPPORTED;
+    // one workgroup per query there
+    if (decode && (dtype != AP_BF16 || sched || (long long)B * H * Lq >= 2147483647LL)) return AP_ERR_UNSUPPORTED;
     // bitmap rows are fetched with 32-bit byte offsets there: 512 bytes per tile
     if (entmax && nQB * ((Lk + 63) / 64) * H >= (1LL << 22)) return AP_ERR_UNSUPPORTED;
     if (splits > 0) {
         if (!workspace || !aligned(workspace, 16)) return AP_ERR_INVALID_ARG;
-        if (dtype != AP_BF16 || block_m != 64) return AP_ERR_UNSUPPORTED;
+        if (dtype != AP_BF16 || (block_m != 64 && !decode)) return AP_ERR_UNSUPPORTED;
         if (splits > 1024 || nQB * H * B * splits >= 2147483647LL) return AP_ERR_UNSUPPORTED;
+        if (decode && (long long)B * H * Lq * splits >= 2147483647LL) return AP_ERR_UNSUPPORTED;
         if (workspace_bytes < ap_fwd_split_workspace_bytes(B, H, Lq, D, splits)) return AP_ERR_CAPACITY;
     }
 
@@ -190,7 +194,9 @@ static ap_status fwd_common(const void* Q, const void* K, const void* V, void* O
     a.part_lse = a.part_o ? a.part_o + (size_t)a.splits * B * H * Lq * D : nullptr;
 
     hipError_t e;
-    if (entmax)
+    if (decode)
+        e = ap::launch_fwd_decode(a, (hipStream_t)stream);
+    else if (entmax)
         e = ap::launch_entmax15_fwd(a, lse, (hipStream_t)stream);
     else if (splits > 0)
         e = ap::launch_fwd_split(a, (hipStream_t)stream);
@@ -212,6 +218,23 @@ ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* 
     return fwd_common(Q, K, V, O, lse, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v, stride_o,
                       row_ptr, col_idx, bitmaps, block_m, block_n, sched, causal, softmax_scale, 0,
                       nullptr, 0, stream);
+}
+
+ap_status ap_sparse_attn_decode(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                const int64_t* stride_q, const int64_t* stride_k,
+                                const int64_t* stride_v, const int64_t* stride_o,
+                                const int32_t* row_ptr, const int32_t* col_idx,
+                                const uint64_t* bitmaps, int block_m, int block_n, int causal,
+                                float softmax_scale, int splits, void* workspace,
+                                size_t workspace_bytes, void* stream)
+{
+    if (splits <= 0) return AP_ERR_INVALID_ARG;
+    // one workgroup per query writes O itself: splits = 1 needs no workspace
+    return fwd_common(Q, K, V, O, lse, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v, stride_o,
+                      row_ptr, col_idx, bitmaps, block_m, block_n, nullptr, causal, softmax_scale,
+                      splits > 1 ? splits : 0, splits > 1 ? workspace : nullptr, workspace_bytes, stream,
+                      false, true);
 }
 
 ap_status ap_sparse_attn_entmax15_fwd(const void* Q, const void* K, const void* V, void* O, float* tau,

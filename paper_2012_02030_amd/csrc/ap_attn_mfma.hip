@@ -606,6 +606,18 @@ hipError_t launch_split_d(const FwdArgs& a, hipStream_t stream)
 
 }  // namespace
 
+hipError_t launch_merge_splits(const FwdArgs& a, hipStream_t stream)
+{
+    const long long rows = (long long)a.B * a.H * a.Lq;
+    switch (a.D) {
+    case 32: hipLaunchKernelGGL(merge_splits_kernel<32>, dim3((unsigned)((rows * 8 + 255) / 256)), dim3(256), 0, stream, a); break;
+    case 64: hipLaunchKernelGGL(merge_splits_kernel<64>, dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, stream, a); break;
+    case 128: hipLaunchKernelGGL(merge_splits_kernel<128>, dim3((unsigned)((rows * 32 + 255) / 256)), dim3(256), 0, stream, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_fwd_split(const FwdArgs& a, hipStream_t stream)
 {
     switch (a.D) {

@@ -56,6 +56,11 @@ hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream);
 // same result, the entries of every block row cut into a.splits chunks and merged (block_m 64)
 hipError_t launch_fwd_split(const FwdArgs& a, hipStream_t stream);
 
+// merges the a.splits partial results in a.part_o / a.part_lse into O and lse (ap_attn_mfma.hip)
+hipError_t launch_merge_splits(const FwdArgs& a, hipStream_t stream);
+// a few queries against many keys, a.splits workgroups per query, no matrix cores (ap_attn_decode.hip)
+hipError_t launch_fwd_decode(const FwdArgs& a, hipStream_t stream);
+
 // ---- 1.5-entmax forward (ap_attn_entmax.hip): bf16, block 64x64, plain layout walk
 hipError_t launch_entmax15_fwd(const FwdArgs& a, float* tau_out, hipStream_t stream);
 

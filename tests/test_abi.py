@@ -351,6 +351,28 @@ def test_cropped_layout_arguments(L):
     assert crop(ws_bytes=ws - 1) == ap.AP_ERR_CAPACITY
 
 
+def test_decode_arguments(L):
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+
+    def dec(**over):
+        a = dict(Q=fake, O=fake + 0x300000, dtype=ap.AP_BF16, D=64, bm=64, bn=64, causal=0, Lq=1, Lk=64)
+        a.update(over)
+        return L.ap_sparse_attn_decode(a["Q"], fake + 0x100000, fake + 0x200000, a["O"], None, a["dtype"], 1, 2,
+                                       a["Lq"], a["Lk"], a["D"], s, s, s, s, fake, fake, fake, a["bm"], a["bn"],
+                                       a["causal"], 0.0, a.get("splits", 1), a.get("ws", None), a.get("wsb", 0), None)
+
+    assert dec(splits=0) == ap.AP_ERR_INVALID_ARG
+    assert dec(splits=4, ws=None) == ap.AP_ERR_INVALID_ARG                     # splits > 1 need a workspace
+    assert dec(splits=4, ws=fake, wsb=16) == ap.AP_ERR_CAPACITY
+    assert dec(Q=None) == ap.AP_ERR_INVALID_ARG
+    assert dec(O=fake) == ap.AP_ERR_INVALID_ARG                                # O aliases Q
+    assert dec(dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    assert dec(D=48) == ap.AP_ERR_UNSUPPORTED
+    assert dec(bn=32) == ap.AP_ERR_UNSUPPORTED
+    assert dec(causal=1, Lq=128, Lk=64) == ap.AP_ERR_INVALID_ARG
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ap, "_lib", None)
     monkeypatch.setattr(ap, "LIB_PATH", "/nonexistent/libap_mi355x.so")
