@@ -331,6 +331,12 @@ def main():
 
         acc_ms = timed(lambda: ap.ap_accumulate_attention_maps(q, k, abar=abar, causal=cfg.causal,
                                                                weight=1.0 / cfg.B), steps)
+        # the same with the row statistics of the unpruned attention call on the same inputs
+        ones_lay = ap.ap_build_layout(torch.ones((cfg.H, cfg.Lq, cfg.Lk), dtype=torch.uint8, device=dev), 64, 64)
+        _, lse_full = ap.ap_sparse_attn_fwd(q, k, k, ones_lay, causal=cfg.causal)
+        del ones_lay
+        acc_lse_ms = timed(lambda: ap.ap_accumulate_attention_maps(q, k, abar=abar, causal=cfg.causal,
+                                                                   weight=1.0 / cfg.B, lse=lse_full), steps)
         abar.zero_()
         ap.ap_accumulate_attention_maps(q, k, abar=abar, causal=cfg.causal, weight=1.0 / cfg.B)
         keep = {}
@@ -355,6 +361,7 @@ def main():
             "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D, "causal": cfg.causal},
             "prune_fraction": p,
             "accumulate_ms": acc_ms,
+            "accumulate_with_given_lse_ms": acc_lse_ms,
             "accumulate_alg_bytes": acc_bytes,
             "accumulate_gbs": acc_bytes / (acc_ms * 1e-3) / 1e9,
             "accumulate_hbm_frac": acc_bytes / (acc_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -436,6 +436,17 @@ ap_status ap_accumulate_attention_maps(const void *Q, const void *K, ap_dtype dt
                                        float weight, float *abar, void *workspace,
                                        size_t workspace_bytes, void *stream);
 
+/* The same when the model's own attention call has already run on these Q and K: `lse` is the
+ * log-sum-exp [B, H, Lq] that ap_sparse_attn_fwd returns for the all-ones mask with the same
+ * `causal` and scale (the unpruned model of step 2 of Section 3.2's procedure computes it anyway).
+ * The pass that would recompute the row statistics is skipped: one small launch and the
+ * accumulation.  Everything else as above, workspace included. */
+ap_status ap_accumulate_attention_maps_lse(const void *Q, const void *K, const float *lse, ap_dtype dtype,
+                                           int B, int H, int Lq, int Lk, int D, const int64_t *stride_q,
+                                           const int64_t *stride_k, int causal, float softmax_scale,
+                                           float weight, float *abar, void *workspace,
+                                           size_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Mask construction, step 2: layer-wise percentile threshold and pruning mask (Section 3.2,
  * paragraph before Eq. (2), and Eq. (2)).

@@ -32,6 +32,7 @@ SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes
            "ap_build_col_schedule", "ap_sparse_attn_bwd_sched",
            "ap_entmax15_bwd_workspace_bytes", "ap_sparse_attn_entmax15_bwd",
            "ap_attention_maps_workspace_bytes", "ap_accumulate_attention_maps",
+           "ap_accumulate_attention_maps_lse",
            "ap_prune_mask_workspace_bytes", "ap_prune_mask")
 
 
@@ -128,6 +129,11 @@ def lib() -> ctypes.CDLL:
                                                    ctypes.POINTER(i64), ctypes.POINTER(i64), i32,
                                                    ctypes.c_float, ctypes.c_float, vp, vp,
                                                    ctypes.c_size_t, vp]
+        L.ap_accumulate_attention_maps_lse.restype = i32
+        L.ap_accumulate_attention_maps_lse.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                                       ctypes.POINTER(i64), ctypes.POINTER(i64), i32,
+                                                       ctypes.c_float, ctypes.c_float, vp, vp,
+                                                       ctypes.c_size_t, vp]
         L.ap_prune_mask_workspace_bytes.restype = ctypes.c_size_t
         L.ap_prune_mask_workspace_bytes.argtypes = []
         L.ap_prune_mask.restype = i32
@@ -557,9 +563,12 @@ def ap_attention_maps_workspace_bytes(B: int, H: int, Lq: int) -> int:
 def ap_accumulate_attention_maps(Q: torch.Tensor, K: torch.Tensor,
                                  abar: Optional[torch.Tensor] = None, causal: bool = False,
                                  softmax_scale: float = 0.0, weight: float = 1.0,
-                                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+                                 stream: Optional[torch.cuda.Stream] = None,
+                                 lse: Optional[torch.Tensor] = None) -> torch.Tensor:
     """abar [H,Lq,Lk] fp32 += weight * sum_b softmax(Q_b K_b^T * scale); a new zeroed abar when
-    none is given.  Q [B,H,Lq,D], K [B,H,Lk,D] bf16 device tensors.  Asynchronous on the stream."""
+    none is given.  Q [B,H,Lq,D], K [B,H,Lk,D] bf16 device tensors.  lse: the log-sum-exp
+    [B,H,Lq] of the unpruned attention call on the same inputs, if it is at hand
+    (ap_accumulate_attention_maps_lse).  Asynchronous on the stream."""
     if Q.dtype != torch.bfloat16 or K.dtype != torch.bfloat16:
         raise ValueError("Q and K must be bfloat16")
     if Q.dim() != 4 or K.dim() != 4:
@@ -576,10 +585,15 @@ def ap_accumulate_attention_maps(Q: torch.Tensor, K: torch.Tensor,
         raise ValueError("abar must be a contiguous float32 tensor [H, Lq, Lk]")
     ws_bytes = ap_attention_maps_workspace_bytes(B, H, Lq)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=Q.device)
-    st = lib().ap_accumulate_attention_maps(
-        Q.data_ptr(), K.data_ptr(), AP_BF16, B, H, Lq, Lk, D, _strides3(Q), _strides3(K),
-        int(bool(causal)), float(softmax_scale), float(weight), abar.data_ptr(), ws.data_ptr(),
-        ws_bytes, _stream_ptr(stream))
+    tail = (AP_BF16, B, H, Lq, Lk, D, _strides3(Q), _strides3(K), int(bool(causal)), float(softmax_scale),
+            float(weight), abar.data_ptr(), ws.data_ptr(), ws_bytes, _stream_ptr(stream))
+    if lse is None:
+        st = lib().ap_accumulate_attention_maps(Q.data_ptr(), K.data_ptr(), *tail)
+    else:
+        if lse.dtype != torch.float32 or tuple(lse.shape) != (B, H, Lq):
+            raise ValueError("lse must be float32 [B, H, Lq]")
+        lse = lse.contiguous()
+        st = lib().ap_accumulate_attention_maps_lse(Q.data_ptr(), K.data_ptr(), lse.data_ptr(), *tail)
     if st != AP_OK:
         raise ApError(st, "ap_accumulate_attention_maps")
     return abar

@@ -455,11 +455,10 @@ size_t ap_attention_maps_workspace_bytes(int B, int H, int Lq)
     return (size_t)B * (size_t)H * (size_t)Lq * sizeof(float);
 }
 
-ap_status ap_accumulate_attention_maps(const void* Q, const void* K, ap_dtype dtype, int B, int H,
-                                       int Lq, int Lk, int D, const int64_t* stride_q,
-                                       const int64_t* stride_k, int causal, float softmax_scale,
-                                       float weight, float* abar, void* workspace,
-                                       size_t workspace_bytes, void* stream)
+static ap_status maps_common(const void* Q, const void* K, const float* lse, ap_dtype dtype, int B, int H,
+                             int Lq, int Lk, int D, const int64_t* stride_q, const int64_t* stride_k,
+                             int causal, float softmax_scale, float weight, float* abar, void* workspace,
+                             size_t workspace_bytes, void* stream)
 {
     if (!Q || !K || !stride_q || !stride_k || !abar || !workspace) return AP_ERR_INVALID_ARG;
     if (B <= 0 || H <= 0 || Lq <= 0 || Lk <= 0 || D <= 0) return AP_ERR_INVALID_ARG;
@@ -471,7 +470,7 @@ ap_status ap_accumulate_attention_maps(const void* Q, const void* K, ap_dtype dt
     if (!(D == 32 || D == 64 || D == 128)) return AP_ERR_UNSUPPORTED;
     const long long nQB = (Lq + 63) / 64, nKB = (Lk + 63) / 64;
     if (nQB * H * B >= 2147483647LL || nQB * nKB * H >= 2147483647LL) return AP_ERR_UNSUPPORTED;
-    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(abar, 16) || !aligned(workspace, 16))
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(abar, 16) || !aligned(workspace, 16) || !aligned(lse, 4))
         return AP_ERR_INVALID_ARG;
     if (!strides_ok(stride_q, D, 8) || !strides_ok(stride_k, D, 8)) return AP_ERR_INVALID_ARG;
     if ((long long)Lk * stride_k[2] * 2 >= 2147483647LL) return AP_ERR_UNSUPPORTED;
@@ -486,7 +485,28 @@ ap_status ap_accumulate_attention_maps(const void* Q, const void* K, ap_dtype dt
     a.weight = weight;
     a.abar = abar;
     a.lse2 = (float*)workspace;
-    return ap::launch_attention_maps(a, (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
+    return ap::launch_attention_maps(a, lse, (hipStream_t)stream) == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
+ap_status ap_accumulate_attention_maps(const void* Q, const void* K, ap_dtype dtype, int B, int H,
+                                       int Lq, int Lk, int D, const int64_t* stride_q,
+                                       const int64_t* stride_k, int causal, float softmax_scale,
+                                       float weight, float* abar, void* workspace,
+                                       size_t workspace_bytes, void* stream)
+{
+    return maps_common(Q, K, nullptr, dtype, B, H, Lq, Lk, D, stride_q, stride_k, causal, softmax_scale,
+                       weight, abar, workspace, workspace_bytes, stream);
+}
+
+ap_status ap_accumulate_attention_maps_lse(const void* Q, const void* K, const float* lse, ap_dtype dtype,
+                                           int B, int H, int Lq, int Lk, int D, const int64_t* stride_q,
+                                           const int64_t* stride_k, int causal, float softmax_scale,
+                                           float weight, float* abar, void* workspace,
+                                           size_t workspace_bytes, void* stream)
+{
+    if (!lse) return AP_ERR_INVALID_ARG;
+    return maps_common(Q, K, lse, dtype, B, H, Lq, Lk, D, stride_q, stride_k, causal, softmax_scale,
+                       weight, abar, workspace, workspace_bytes, stream);
 }
 
 size_t ap_prune_mask_workspace_bytes(void) { return ap::prune_mask_workspace_bytes(); }

@@ -114,7 +114,9 @@ struct MapArgs {
     float* abar;                    // [H, Lq, Lk], accumulated into
     float* lse2;                    // [B, H, Lq] scratch: base-2 log-sum-exp of each score row
 };
-hipError_t launch_attention_maps(const MapArgs& a, hipStream_t stream);
+// lse: null (the row statistics are computed by a pass of their own), or the natural-log
+// log-sum-exp [B, H, Lq] of the same scores, as the attention forward call returns it
+hipError_t launch_attention_maps(const MapArgs& a, const float* lse, hipStream_t stream);
 
 // ---- mask construction: percentile threshold and mask (ap_threshold.hip)
 size_t prune_mask_workspace_bytes();

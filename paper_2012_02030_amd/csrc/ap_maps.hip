@@ -299,13 +299,28 @@ __global__ __launch_bounds__(64 * NW) void map_accumulate_kernel(MapArgs a, int 
     }
 }
 
+// lse2 = lse * log2(e): the row statistics as the attention forward call returns them (natural
+// logarithm), in the form the accumulation kernel reads.
+__global__ __launch_bounds__(256) void lse_to_base2_kernel(const float* __restrict__ lse, float* __restrict__ lse2,
+                                                            long long n)
+{
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) lse2[i] = lse[i] * kLog2e;                    // -inf (a query without keys) stays -inf
+}
+
 template <int D>
-hipError_t launch_d(const MapArgs& a, hipStream_t stream)
+hipError_t launch_d(const MapArgs& a, const float* lse, hipStream_t stream)
 {
     constexpr int NW = 4, KT = 2;
     const int nQB = (a.Lq + 32 * NW - 1) / (32 * NW), nKG = (a.Lk + 64 * KT - 1) / (64 * KT);
-    hipLaunchKernelGGL((row_lse_kernel<D, NW>), dim3((unsigned)(a.B * a.H * nQB)), dim3(64 * NW), 0,
-                       stream, a, nQB);
+    if (lse) {
+        const long long n = (long long)a.B * a.H * a.Lq;
+        hipLaunchKernelGGL(lse_to_base2_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, lse,
+                           a.lse2, n);
+    } else {
+        hipLaunchKernelGGL((row_lse_kernel<D, NW>), dim3((unsigned)(a.B * a.H * nQB)), dim3(64 * NW), 0,
+                           stream, a, nQB);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((map_accumulate_kernel<D, NW, KT>), dim3((unsigned)(a.H * nQB * nKG)),
@@ -315,12 +330,12 @@ hipError_t launch_d(const MapArgs& a, hipStream_t stream)
 
 }  // namespace
 
-hipError_t launch_attention_maps(const MapArgs& a, hipStream_t stream)
+hipError_t launch_attention_maps(const MapArgs& a, const float* lse, hipStream_t stream)
 {
     switch (a.D) {
-        case 32: return launch_d<32>(a, stream);
-        case 64: return launch_d<64>(a, stream);
-        case 128: return launch_d<128>(a, stream);
+        case 32: return launch_d<32>(a, lse, stream);
+        case 64: return launch_d<64>(a, lse, stream);
+        case 128: return launch_d<128>(a, lse, stream);
     }
     return hipErrorInvalidValue;
 }

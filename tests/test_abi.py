@@ -145,6 +145,18 @@ def test_mask_construction_arguments(L):
     bad = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 60)
     assert acc(sk=bad) == ap.AP_ERR_INVALID_ARG
 
+    def acc_lse(lse=fake + 0x200000, **over):
+        a = dict(Q=fake, ws_bytes=ws, dtype=ap.AP_BF16)
+        a.update(over)
+        return L.ap_accumulate_attention_maps_lse(a["Q"], fake + 0x100000, lse, a["dtype"], 1, 2, 64, 64, 64, s, s,
+                                                  0, 0.0, 1.0, fake, fake, a["ws_bytes"], None)
+
+    assert acc_lse(lse=None) == ap.AP_ERR_INVALID_ARG
+    assert acc_lse(lse=fake + 2) == ap.AP_ERR_INVALID_ARG                      # not 4-byte aligned
+    assert acc_lse(Q=None) == ap.AP_ERR_INVALID_ARG
+    assert acc_lse(dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    assert acc_lse(ws_bytes=ws - 1) == ap.AP_ERR_CAPACITY
+
     wp = ap.ap_prune_mask_workspace_bytes()
     assert wp == 64 + 32768 * 8 + (1 << 20) * (4 + 8)      # state, histogram, candidate keys and indices
 

@@ -58,6 +58,26 @@ def test_mean_map_matches_oracle(case):
     assert err <= MAP_TOL, "max |abar - oracle| = %.3e" % err
 
 
+@pytest.mark.parametrize("case", MAP_CASES[:7], ids=lambda c: "B%d_H%d_%dx%d_D%d_%s" % (c[:5] + ("causal" if c[5] else "full",)))
+def test_mean_map_with_the_forward_calls_lse(case):
+    """ap_accumulate_attention_maps_lse: the row statistics come from the unpruned attention call
+    (all-ones mask) on the same inputs instead of a pass of their own; same oracle, same bar."""
+    B, H, Lq, Lk, D, causal = case
+    Q, K = synth.make_qk_positional(B, H, Lq, Lk, D, seed=Lq + Lk + D)
+    dq, rq = to_device(Q, "bf16")
+    dk, rk = to_device(K, "bf16")
+    ones = torch.ones((H, Lq, Lk), dtype=torch.uint8, device="cuda")
+    lay = ap.ap_build_layout(ones, 64, 64)
+    _, lse = ap.ap_sparse_attn_fwd(dq, dk, dk, lay, causal=causal)       # V plays no role in lse
+    abar = ap.ap_accumulate_attention_maps(dq, dk, causal=causal, weight=1.0 / B, lse=lse)
+    torch.cuda.synchronize()
+    ref = oracle.mean_attention_map(rq, rk, causal=causal)
+    got = abar.double().cpu().numpy()
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref).max()
+    assert err <= MAP_TOL, "max |abar - oracle| = %.3e" % err
+
+
 def test_hidden_entries_are_not_touched():
     B, H, Lq, Lk, D = 2, 2, 130, 200, 64
     Q, K = synth.make_qk_positional(B, H, Lq, Lk, D, seed=5)
