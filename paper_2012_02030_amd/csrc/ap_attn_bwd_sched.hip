@@ -194,7 +194,7 @@ __global__ __launch_bounds__(128, D == 128 ? 1 : 2) void bwd_dq_sched_kernel(Bwd
 }
 
 template <int D, int NORM>
-__global__ __launch_bounds__(128, 1) void bwd_dkv_sched_kernel(BwdArgs a, int nKB)
+__global__ __launch_bounds__(128, D == 128 ? 1 : 2) void bwd_dkv_sched_kernel(BwdArgs a, int nKB)
 {
     constexpr int TILE = kBN * D;
     constexpr int KSTEPS = D / 16;
