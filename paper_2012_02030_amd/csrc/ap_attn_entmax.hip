@@ -14,7 +14,11 @@
 //               with its root in [-1, 0); started at -1 (where h >= 0 because the maximum
 //               contributes 1) the steps increase monotonically to the root and never pass it.
 //               The norm is much closer to linear than its square, which saves about half of
-//               the sweeps.  The block row iterates until every row has | |d|^2 - 1 | <= 1e-5.
+//               the sweeps.  A row is done when | |d|^2 - 1 | <= 1e-5 at its tau, or after the
+//               step taken from a tau with | |d|^2 - 1 | <= 1e-2: the steps converge quadratically,
+//               so that step leaves a residual of a few 1e-5 at most (the output is divided by
+//               the actual sum of P in any case) and the sweep that would only confirm it is
+//               saved.  The block row sweeps until all its rows are done.
 //   last sweep  P = [y - tau]_+^2, O^T += V^T P^T, O / sum P.
 //
 // Same operand layouts, LDS swizzles and LDS-direct loads as the softmax kernel; walks the
@@ -32,8 +36,10 @@ namespace {
 using namespace mfma;
 
 constexpr float kEntmaxTol = 1e-5f;          // on sum p - 1
+constexpr float kEntmaxEarly = 1e-2f;        // residual from which one more step is taken unconfirmed
 constexpr int kEntmaxMaxIter = 60;
 constexpr int kEntmaxSchedEntries = 64;      // a block row with more schedule entries walks the layout instead
+constexpr int kEntmaxGathered = 16;          // ... or with more gathered entries among them
 
 template <int D>
 __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* tau_out, int nQB)
@@ -45,7 +51,7 @@ __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* 
     constexpr int RPI = 64 / (D / 8);                        // tile rows per load instruction
     constexpr int NLOAD = (D / 8) / 2;                       // load instructions per wavefront and tile
     __shared__ __attribute__((aligned(1024))) uint16_t smem[2 * STAGE];
-    __shared__ int32_t s_cols[kEntmaxSchedEntries][64];      // gather keys of the block row's entries
+    __shared__ int32_t s_cols[kEntmaxGathered][64];          // gather keys of the block row's gathered entries
     lds_u16* lds = (lds_u16*)smem;
 
     const int tid = threadIdx.x;
@@ -88,11 +94,20 @@ __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* 
     // With a visit schedule the entries of the block row replace its tiles: runs of 64 consecutive
     // keys or 64 gathered keys, causal limit already folded into their bitmaps.  The gather keys
     // are read every sweep, so they are copied to LDS once.
-    const bool use_sched = a.sched.cnt != nullptr && a.sched.cnt[r] <= kEntmaxSchedEntries;
+    bool use_sched = a.sched.cnt != nullptr && a.sched.cnt[r] <= kEntmaxSchedEntries;
+    uint64_t gathered = 0;                                   // bit e: entry e of the block row is gathered
+    if (use_sched) {
+        const int ne = a.sched.cnt[r];
+        gathered = __ballot(lane < ne && a.sched.start[t0 + lane] < 0);
+        use_sched = __popcll(gathered) <= kEntmaxGathered;
+    }
     if (use_sched) {
         t1 = t0 + a.sched.cnt[r];
-        for (int i = tid; i < (t1 - t0) * 64; i += 128)
-            s_cols[i >> 6][i & 63] = a.sched.start[t0 + (i >> 6)] < 0 ? a.sched.cols[(size_t)t0 * 64 + i] : 0;
+        int slot = 0;
+        for (uint64_t mm = gathered; mm; mm &= mm - 1, ++slot) {
+            const int e = __ffsll((long long)mm) - 1;
+            if (tid < 64) s_cols[slot][tid] = a.sched.cols[(size_t)(t0 + e) * 64 + tid];
+        }
     } else if (a.causal) {                                   // columns ascend: hidden tiles are at the end
         while (t1 > t0 && (long long)a.col_idx[t1 - 1] * kBN > block_diag) --t1;
     }
@@ -122,8 +137,9 @@ __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* 
                 if (with_v) issue_tile_loads<D, 2, true>(v_rsrc, lds + STAGE, k0, sv_bytes, wave, lane);
             } else {                                         // gathered entry: an empty slot holds Lk (reads zeros)
                 int gk[NLOAD];
+                const int slot = __popcll(gathered & ((1ull << (t - t0)) - 1ull));
 #pragma unroll
-                for (int u = 0; u < NLOAD; ++u) gk[u] = s_cols[t - t0][(wave + 2 * u) * RPI + g_row];
+                for (int u = 0; u < NLOAD; ++u) gk[u] = s_cols[slot][(wave + 2 * u) * RPI + g_row];
                 issue_gather_loads<D, 2, false>(k_rsrc, base, gk, sk_bytes, wave, lane);
                 if (with_v) issue_gather_loads<D, 2, true>(v_rsrc, lds + STAGE, gk, sv_bytes, wave, lane);
             }
@@ -213,6 +229,7 @@ __global__ __launch_bounds__(128, 2) void entmax15_fwd_kernel(FwdArgs a, float* 
             } else {
                 const float nd = sqrtf(g2);
                 tau = fminf(fmaxf(tau + (nd - 1.0f) * nd / g1, -1.0f), 0.f);
+                done = fabsf(f) <= kEntmaxEarly;             // this step is the last one
             }
         }
     }
