@@ -49,7 +49,7 @@ using namespace mfma;
 // each, which write a normalised fp32 partial output and its log-sum-exp for merge_splits_kernel
 // (few queries against many keys: one workgroup per block row would leave the chip idle).
 template <int D, int NW, int STAGES, bool SCHED, bool SPLIT = false>
-__global__ __launch_bounds__(64 * NW, 2) void fwd_mfma_kernel(FwdArgs a, int nQB, int xcd_chunk)
+__global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd_mfma_kernel(FwdArgs a, int nQB, int xcd_chunk)
 {
     constexpr int BM = 32 * NW;
     constexpr int KSTEPS = D / 16;                           // contraction steps of Q K^T
@@ -630,13 +630,15 @@ hipError_t launch_fwd_split(const FwdArgs& a, hipStream_t stream)
 
 hipError_t launch_fwd_mfma(const FwdArgs& a, hipStream_t stream)
 {
-    // 64-query block rows: two wavefronts and at most 32 KB of LDS (one stage at D = 128, two
-    // below), so that four workgroups share a CU and hide each other's load latency.
+    // 64-query block rows: two wavefronts and one LDS stage at D = 128 (32 KB, four workgroups per
+    // CU) and at D = 64 (16 KB and at most 168 registers: six workgroups per CU, which matters for
+    // short sequences where a workgroup's life is mostly waiting for its first loads); two stages
+    // at D = 32.
     // 128-query block rows: four wavefronts and two LDS stages, two workgroups per CU.
     const bool wide = a.block_m == 128;
     switch (a.D) {
     case 32: return wide ? launch_one<32, 4, 2>(a, stream) : launch_one<32, 2, 2>(a, stream);
-    case 64: return wide ? launch_one<64, 4, 2>(a, stream) : launch_one<64, 2, 2>(a, stream);
+    case 64: return wide ? launch_one<64, 4, 2>(a, stream) : launch_one<64, 2, 1>(a, stream);
     case 128: return wide ? launch_one<128, 4, 2>(a, stream) : launch_one<128, 2, 1>(a, stream);
     default: return hipErrorInvalidValue;
     }
