@@ -193,8 +193,10 @@ __global__ __launch_bounds__(128, D == 128 ? 1 : 2) void bwd_dq_sched_kernel(Bwd
                        dQp + (size_t)(qb * 64 + wave * 32) * a.sq[2], a.sq[2], a.Lq - (qb * 64 + wave * 32));
 }
 
+// Two wavefronts per SIMD where the registers allow it without spilling (the 1.5-entmax form at
+// D = 64 needs a few more than 256).
 template <int D, int NORM>
-__global__ __launch_bounds__(128, D == 128 ? 1 : 2) void bwd_dkv_sched_kernel(BwdArgs a, int nKB)
+__global__ __launch_bounds__(128, (D == 128 || (D == 64 && NORM == 1)) ? 1 : 2) void bwd_dkv_sched_kernel(BwdArgs a, int nKB)
 {
     constexpr int TILE = kBN * D;
     constexpr int KSTEPS = D / 16;
