@@ -10,12 +10,14 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libap_mi355x.so")
+RESOURCES = os.path.join(PKG, "libap_mi355x.resources.txt")   # per-kernel registers, spills, LDS
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
+    "-Rpass-analysis=kernel-resource-usage", "-fno-caret-diagnostics",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 
@@ -24,8 +26,28 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def kernel_resources(compiler_output: str) -> list:
+    """Per-kernel figures from the compiler's resource-usage remarks: one dict per kernel."""
+    kernels, cur = [], None
+    for line in compiler_output.splitlines():
+        if "remark:" not in line:
+            continue
+        text = line.split("remark:", 1)[1].split("[-Rpass", 1)[0].strip()
+        if text.startswith("Function Name:"):
+            cur = {"name": text.split(":", 1)[1].strip()}
+            kernels.append(cur)
+        elif cur is not None and ":" in text:
+            key, val = text.split(":", 1)
+            cur[key.strip()] = val.strip()
+    return kernels
+
+
 def build(verbose: bool = False, extra=()) -> str:
-    """Compile every HIP source into libap_mi355x.so next to this file and return its path."""
+    """Compile every HIP source into libap_mi355x.so next to this file and return its path.
+
+    Fails if any kernel spills registers: spilled values travel through the same in-order vector
+    memory path as the tile loads, and a reload inside a tile loop then waits for the tiles in
+    flight."""
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [HIPCC, *FLAGS, *extra, *sources(), "-o", tmp]
     if verbose:
@@ -37,8 +59,20 @@ def build(verbose: bool = False, extra=()) -> str:
         if os.path.exists(tmp):
             os.remove(tmp)
         raise RuntimeError("hipcc failed:\n" + out)
+    kernels = kernel_resources(out)
+    out = "\n".join(line for line in out.splitlines() if "-Rpass-analysis=kernel-resource-usage" not in line)
     if verbose and out.strip():
         print(out)
+    with open(RESOURCES, "w") as f:
+        for k in kernels:
+            f.write("%s  VGPRs %s  AGPRs %s  spilled VGPRs %s  spilled SGPRs %s  waves/SIMD %s  LDS %s\n" % (
+                k["name"], k.get("VGPRs", "?"), k.get("AGPRs", "?"), k.get("VGPRs Spill", "?"),
+                k.get("SGPRs Spill", "?"), k.get("Occupancy [waves/SIMD]", "?"),
+                k.get("LDS Size [bytes/block]", "?")))
+    spilling = [k["name"] for k in kernels if k.get("VGPRs Spill", "0") != "0"]
+    if spilling:
+        os.remove(tmp)
+        raise RuntimeError("kernels that spill vector registers: " + ", ".join(spilling))
     os.replace(tmp, LIB)
     return LIB
 

@@ -390,3 +390,26 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ap, "LIB_PATH", "/nonexistent/libap_mi355x.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         ap.lib()
+
+
+def test_build_reports_kernel_resources_and_no_spills():
+    """The build parses the compiler's per-kernel resource remarks; a kernel that spills vector
+    registers fails the build (a reload inside a tile loop waits for the tile loads in flight)."""
+    from paper_2012_02030_amd import build as b
+
+    sample = "\n".join([
+        "x.hip:1:1: remark: Function Name: k1 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:1:1: remark:     VGPRs: 12 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:1:1: remark:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:9:1: remark: Function Name: k2 [-Rpass-analysis=kernel-resource-usage]",
+        "x.hip:9:1: remark:     VGPRs Spill: 7 [-Rpass-analysis=kernel-resource-usage]",
+        "warning: something else",
+    ])
+    ks = b.kernel_resources(sample)
+    assert [k["name"] for k in ks] == ["k1", "k2"]
+    assert ks[0]["VGPRs"] == "12" and ks[0]["VGPRs Spill"] == "0" and ks[1]["VGPRs Spill"] == "7"
+    # the figures of the library that is loaded by the tests, if it was built in this tree
+    if os.path.exists(b.RESOURCES):
+        lines = open(b.RESOURCES).read().splitlines()
+        assert len(lines) > 20
+        assert all("spilled VGPRs 0" in line for line in lines), [l for l in lines if "spilled VGPRs 0" not in l]
