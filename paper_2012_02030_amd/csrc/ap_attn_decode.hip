@@ -4,13 +4,18 @@
 //
 // With one to a few queries per (example, head) there is nothing for the matrix cores to do: a
 // 64-query tile would be empty but for a row or two.  The work is reading the kept keys' K and V
-// rows, so it is laid out for that: `splits` workgroups of 16 wavefronts per query, each with a
-// contiguous share of the stored tiles of the query's block row; the lanes of a wavefront span the
-// head dimension (one K row or V row is one coalesced read of the wavefront); the wavefronts
-// share out the workgroup's tiles, walk the set bits of the query's bitmap words, and each keeps
-// an online softmax over its keys in fp32; the 16 partial results are merged through LDS, and
-// those of several workgroups by the split forward call's merge kernel.  Keys are taken eight at
-// a time, so that sixteen row reads are in flight per wavefront.
+// rows, so it is laid out for that.  `splits` workgroups of 16 wavefronts per query, each with a
+// contiguous share of the stored tiles of the query's block row.  A workgroup
+//   1. turns the bitmap words of up to 128 tiles at a time into the list of kept visible keys in
+//      LDS (one thread per tile, a prefix sum of the population counts gives every thread its
+//      place in the list), so that what follows is a flat loop over keys;
+//   2. runs one online-softmax stream per group of D / 8 lanes: a lane holds 8 elements of the
+//      query and of the output, a K or V row is one 16-byte load per lane of the group (a
+//      wavefront instruction fetches 64 / (D / 8) rows), the dot product is 8 multiply-adds and a
+//      sum over the group with data-parallel-primitive moves inside a 16-lane row; stream s takes
+//      keys s, s + S, s + 2 S, ... of the list, four keys of every stream are in flight at a time;
+//   3. merges the streams of a wavefront by lane exchanges, the 16 wavefronts through LDS, and
+//      those of several workgroups by the split forward call's merge kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -34,72 +39,76 @@ __device__ __forceinline__ uint32_t bf16_rne(float f)
     return u >> 16;
 }
 
-// Sum over the 64 lanes with data-parallel-primitive moves (register to register, no LDS
-// round trip per step): pairs, quads, half rows and rows by mirrored exchanges, then the row
-// totals are passed on to the following rows; lane 63 ends up with the total, which is returned
-// to every lane.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_step(float v)
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
 {
-    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false);
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
     return v + __int_as_float(moved);
 }
-__device__ __forceinline__ float wave_sum(float v)
+// Sum over aligned groups of LPK = 4, 8 or 16 lanes; every lane of a group gets the group's sum.
+template <int LPK>
+__device__ __forceinline__ float group_sum(float v)
 {
-    v = dpp_step<0xB1, 0xf>(v);                              // quad_perm [1,0,3,2]
-    v = dpp_step<0x4E, 0xf>(v);                              // quad_perm [2,3,0,1]
-    v = dpp_step<0x141, 0xf>(v);                             // row_half_mirror
-    v = dpp_step<0x140, 0xf>(v);                             // row_mirror: every lane holds its row's sum
-    v = dpp_step<0x142, 0xa>(v);                             // row_bcast15 into rows 1 and 3
-    v = dpp_step<0x143, 0xc>(v);                             // row_bcast31 into rows 2 and 3
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+    v = dpp_add<0xB1>(v);                                    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);                                    // quad_perm [2,3,0,1]
+    if (LPK >= 8) v = dpp_add<0x141>(v);                     // row_half_mirror
+    if (LPK >= 16) v = dpp_add<0x140>(v);                    // row_mirror
+    return v;
 }
 
-// A lane holds E = 2 consecutive elements of a row (D = 128), 1 (D = 64), or 1 on the first 32
-// lanes (D = 32): LPR = D / E lanes carry a row.
+// 2^(a - b) for a <= b, with 2^(-inf - -inf) = 1 (a stream that has seen no key keeps its zeros)
+__device__ __forceinline__ float scale_to(float a, float b)
+{
+    return a == b ? 1.0f : __builtin_amdgcn_exp2f(a - b);
+}
+
 template <int D>
 __global__ __launch_bounds__(64 * kWaves) void decode_kernel(FwdArgs a, int nQB)
 {
-    constexpr int E = D == 128 ? 2 : 1;
-    constexpr int LPR = D / E;
-    constexpr int U = 8;                                     // keys per step
+    constexpr int LPK = D / 8;                               // lanes per key row
+    constexpr int SPW = 64 / LPK;                            // streams per wavefront
+    constexpr int NS = kWaves * SPW;                         // streams per workgroup
+    constexpr int CHUNK = 128;                               // tiles per pass
+    constexpr int LCAP = CHUNK * 64;                         // keys per pass at most
+    constexpr int UN = 4;                                    // keys of a stream in flight
+    constexpr int E = D == 128 ? 2 : 1;                      // final merge: elements per lane
+    static_assert(kWaves * D <= LCAP, "the merge area reuses the key list");
+    __shared__ int s_list[LCAP];                             // kept visible keys; later the merge area
+    __shared__ int s_wsum[2];
     __shared__ float s_m[kWaves], s_l[kWaves];
-    __shared__ float s_o[kWaves][D];
 
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int sub = lane % LPK;                              // which 8 elements of a row
+    const int strm = wave * SPW + lane / LPK;                // this lane's stream
     const int split = blockIdx.x % a.splits;
     const int row_id = blockIdx.x / a.splits;
     const int i = row_id % a.Lq;                             // query
     const int h = (row_id / a.Lq) % a.H;
     const int b = row_id / (a.Lq * a.H);
-    const bool live = lane < LPR;                            // lanes that carry row elements
 
     const uint16_t* Qp = (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1] + (size_t)i * a.sq[2];
     const uint16_t* Kp = (const uint16_t*)a.K + (size_t)b * a.sk[0] + (size_t)h * a.sk[1];
     const uint16_t* Vp = (const uint16_t*)a.V + (size_t)b * a.sv[0] + (size_t)h * a.sv[1];
 
-    // one row's elements of this lane, as fp32
-    auto load_row = [&](const uint16_t* row, float* x) {
-        if (E == 2) {
-            const uint32_t w = live ? *reinterpret_cast<const uint32_t*>(row + 2 * lane) : 0u;
-            x[0] = bf16_lo(w);
-            x[E - 1] = bf16_hi(w);
-        } else {
-            x[0] = live ? bf16_lo(row[lane]) : 0.f;
-        }
+    auto unpack8 = [](const uint4& w, float* x) {
+        x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x); x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
+        x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z); x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
     };
 
-    float q[E];
-    load_row(Qp, q);
-    const float sc = a.scale * kLog2e;
+    float q[8];
+    {
+        const uint4 w = *reinterpret_cast<const uint4*>(Qp + 8 * sub);
+        unpack8(w, q);
+        const float sc = a.scale * kLog2e;                   // scores come out in the log2 domain
 #pragma unroll
-    for (int e = 0; e < E; ++e) q[e] *= sc;                  // scores come out in the log2 domain
-
-    float m = -INFINITY, l = 0.f;                            // wave-uniform running maximum and sum
-    float o[E];
+        for (int e = 0; e < 8; ++e) q[e] *= sc;
+    }
+    float m = -INFINITY, l = 0.f;                            // this stream's running maximum and sum
+    float o[8];
 #pragma unroll
-    for (int e = 0; e < E; ++e) o[e] = 0.f;
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
 
     const int r = h * nQB + i / a.block_m;
     const int rr = i % a.block_m;
@@ -111,82 +120,98 @@ __global__ __launch_bounds__(64 * kWaves) void decode_kernel(FwdArgs a, int nQB)
         t1 = min(t1, t0 + per);
     }
 
-    auto fold = [&](const int* key, int n) {                 // n <= U keys, wave-uniform
-        float kx[U][E], vx[U][E];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (u < n) {
-                load_row(Kp + (size_t)key[u] * a.sk[2], kx[u]);
-                load_row(Vp + (size_t)key[u] * a.sv[2], vx[u]);
-            }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (u < n) {
-                float part = 0.f;
-#pragma unroll
-                for (int e = 0; e < E; ++e) part = fmaf(q[e], kx[u][e], part);
-                const float s = wave_sum(part);
-                const float m_new = fmaxf(m, s);
-                const float alpha = __builtin_amdgcn_exp2f(m - m_new);   // 0 when m was -inf
-                const float p = __builtin_amdgcn_exp2f(s - m_new);
-                l = fmaf(l, alpha, p);
-#pragma unroll
-                for (int e = 0; e < E; ++e) o[e] = fmaf(o[e], alpha, p * vx[u][e]);
-                m = m_new;
-            }
-    };
-
-    // The workgroup's tiles are dealt to the wavefronts in contiguous groups of G <= 64; a group's
-    // block columns and bitmap words are fetched with one load per lane, so that the walk over the
-    // kept keys does not wait for memory once per tile.
-    int key[U], nkey = 0;
-    const int G = min(64, max(1, (t1 - t0 + kWaves - 1) / kWaves));
-    for (int base = t0 + wave * G; base < t1; base += kWaves * G) {
-        const int t = base + lane;
-        int k0_v = 0;
-        uint64_t word_v = 0;
-        if (lane < G && t < t1) {
-            k0_v = a.col_idx[t] * 64;
-            word_v = a.bitmaps[(size_t)t * a.block_m + rr];
+    for (int c0 = t0; c0 < t1; c0 += CHUNK) {                // workgroup-uniform trip count
+        // ---- 1. the kept visible keys of tiles c0 .. c0 + CHUNK - 1, ascending, into s_list
+        uint64_t word = 0;
+        int k0 = 0;
+        if (tid < CHUNK && c0 + tid < t1) {
+            const int t = c0 + tid;
+            k0 = a.col_idx[t] * 64;
+            word = a.bitmaps[(size_t)t * a.block_m + rr];
             if (a.causal) {
-                const long long lim = diag - k0_v;
-                if (lim < 0) word_v = 0;
-                else if (lim < 63) word_v &= (2ull << lim) - 1ull;
+                const long long lim = diag - k0;
+                if (lim < 0) word = 0;
+                else if (lim < 63) word &= (2ull << lim) - 1ull;
             }
         }
-        unsigned long long tiles = __ballot(word_v != 0);
-        while (tiles) {
-            const int src = __ffsll((long long)tiles) - 1;
-            tiles &= tiles - 1;
-            const int k0 = __builtin_amdgcn_readlane(k0_v, src);
-            uint64_t word = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(word_v >> 32), src) << 32) |
-                            (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)word_v, src);
+        const int cnt = __popcll(word);
+        int incl = cnt;                                      // inclusive prefix sum inside the wavefront
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += up;
+        }
+        if (wave < 2 && lane == 63) s_wsum[wave] = incl;     // CHUNK = 128 tiles: two wavefronts hold them
+        __syncthreads();                                     // also: the previous pass is done with s_list
+        const int n = s_wsum[0] + s_wsum[1];                 // keys of this pass
+        {
+            int pos = incl - cnt + (wave == 1 ? s_wsum[0] : 0);
             while (word) {
                 const int j = __ffsll((long long)word) - 1;
                 word &= word - 1;
+                s_list[pos++] = k0 + j;
+            }
+        }
+        __syncthreads();
+
+        // ---- 2. stream `strm` folds keys strm, strm + NS, ... of the list
+        for (int base = 0; base < n; base += UN * NS) {
+            uint4 kx[UN], vx[UN];
+            bool valid[UN];
 #pragma unroll
-                for (int u = 0; u < U; ++u)                  // key[nkey] = k0 + j without indexing registers
-                    if (u == nkey) key[u] = k0 + j;
-                if (++nkey == U) {
-                    fold(key, U);
-                    nkey = 0;
-                }
+            for (int u = 0; u < UN; ++u) {
+                const int idx = base + u * NS + strm;
+                valid[u] = idx < n;
+                const int key = s_list[valid[u] ? idx : 0];  // n > 0 here: slot 0 is a real key
+                kx[u] = *reinterpret_cast<const uint4*>(Kp + (size_t)key * a.sk[2] + 8 * sub);
+                vx[u] = *reinterpret_cast<const uint4*>(Vp + (size_t)key * a.sv[2] + 8 * sub);
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                float x[8];
+                unpack8(kx[u], x);
+                float part = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) part = fmaf(q[e], x[e], part);
+                const float s = group_sum<LPK>(part);
+                const float m_new = valid[u] ? fmaxf(m, s) : m;
+                const float alpha = scale_to(m, m_new);
+                const float p = valid[u] ? __builtin_amdgcn_exp2f(s - m_new) : 0.f;
+                l = fmaf(l, alpha, p);
+                unpack8(vx[u], x);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = fmaf(o[e], alpha, p * x[e]);
+                m = m_new;
             }
         }
     }
-    if (nkey > 0) fold(key, nkey);
 
-    // merge the wavefronts' partial results: O = sum_w 2^(m_w - M) o_w / sum_w 2^(m_w - M) l_w
+    // ---- 3. merge: the streams of a wavefront by lane exchanges ...
+#pragma unroll
+    for (int off = LPK; off < 64; off <<= 1) {
+        const float m2 = __shfl_xor(m, off, 64);
+        const float l2 = __shfl_xor(l, off, 64);
+        const float M = fmaxf(m, m2);
+        const float f1 = scale_to(m, M), f2 = scale_to(m2, M);
+        l = l * f1 + l2 * f2;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = o[e] * f1 + __shfl_xor(o[e], off, 64) * f2;
+        m = M;
+    }
+    // ... the wavefronts through LDS: O = sum_w 2^(m_w - M) o_w / sum_w 2^(m_w - M) l_w
+    __syncthreads();                                         // everybody is done with the key list
+    float* s_o = reinterpret_cast<float*>(s_list);           // [kWaves][D]
     if (lane == 0) {
         s_m[wave] = m;
         s_l[wave] = l;
     }
-    if (live) {
+    if (lane < LPK) {
 #pragma unroll
-        for (int e = 0; e < E; ++e) s_o[wave][E * lane + e] = o[e];
+        for (int e = 0; e < 8; ++e) s_o[wave * D + 8 * lane + e] = o[e];
     }
     __syncthreads();
     if (wave == 0) {
+        const bool live = lane < D / E;                      // lanes that carry row elements
         float M = -INFINITY;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) M = fmaxf(M, s_m[w]);
@@ -198,7 +223,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_kernel(FwdArgs a, int nQB)
             L = fmaf(s_l[w], f, L);
             if (live) {
 #pragma unroll
-                for (int e = 0; e < E; ++e) acc[e] = fmaf(s_o[w][E * lane + e], f, acc[e]);
+                for (int e = 0; e < E; ++e) acc[e] = fmaf(s_o[w * D + E * lane + e], f, acc[e]);
             }
         }
         const float inv = L > 0.f ? 1.f / L : 0.f;           // no visible kept key: O = 0
