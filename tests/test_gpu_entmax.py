@@ -118,3 +118,19 @@ def test_entmax_block_row_with_more_than_64_schedule_entries():
     Q, K, V = rand_qkv(11, 1, 1, 64, 5000, 64)
     mask = np.ones((1, 64, 5000), np.uint8)
     run_entmax(Q, K, V, mask, False)
+
+
+def test_entmax_block_row_with_more_than_16_gathered_entries():
+    """Sparse 64 x 3000 mask (2 % kept, about 45 distinct columns per tile): every tile of the one
+    block row is packed, into more gathered entries than the kernel keeps keys for in LDS, so it
+    walks the layout's tiles; a 64 x 900 mask of the same kind stays within the limit."""
+    for Lk, seed in ((3000, 12), (900, 13)):
+        print("entmax gathered", Lk, flush=True)
+        Q, K, V = rand_qkv(seed, 1, 1, 64, Lk, 64, gain=2.0)
+        mask = synth.random_mask(1, 64, Lk, 0.02, seed=seed)
+        lay = ap.ap_build_layout(torch.from_numpy(mask).cuda(), 64, 64)
+        sched = ap.ap_build_schedule(lay, causal=False)
+        torch.cuda.synchronize()
+        n_gathered = int((sched.start[: int(sched.cnt[0].item())] < 0).sum().item())
+        assert (n_gathered > 16) == (Lk == 3000), n_gathered
+        run_entmax(Q, K, V, mask, False)
