@@ -45,9 +45,10 @@ def kernel_resources(compiler_output: str) -> list:
 def build(verbose: bool = False, extra=()) -> str:
     """Compile every HIP source into libap_mi355x.so next to this file and return its path.
 
-    Fails if any kernel spills registers: spilled values travel through the same in-order vector
-    memory path as the tile loads, and a reload inside a tile loop then waits for the tiles in
-    flight."""
+    Writes the per-kernel register, spill and LDS figures next to the library and warns if any
+    kernel spills vector registers: spilled values travel through the same in-order vector memory
+    path as the tile loads, and a reload inside a tile loop then waits for the tiles in flight
+    (tests/test_abi.py asserts that there is none)."""
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [HIPCC, *FLAGS, *extra, *sources(), "-o", tmp]
     if verbose:
@@ -70,9 +71,8 @@ def build(verbose: bool = False, extra=()) -> str:
                 k.get("SGPRs Spill", "?"), k.get("Occupancy [waves/SIMD]", "?"),
                 k.get("LDS Size [bytes/block]", "?")))
     spilling = [k["name"] for k in kernels if k.get("VGPRs Spill", "0") != "0"]
-    if spilling:
-        os.remove(tmp)
-        raise RuntimeError("kernels that spill vector registers: " + ", ".join(spilling))
+    if spilling:                                             # the library still works; the tests flag it
+        print("WARNING: kernels that spill vector registers: " + ", ".join(spilling), flush=True)
     os.replace(tmp, LIB)
     return LIB
 
