@@ -49,6 +49,12 @@ SPLIT_CASES = [
     (1, 2, 100, 3000, 32, True, 0.05, 7, True),       # two block rows, ragged
     (1, 1, 8, 300, 64, True, 0.02, 64, False),        # more splits than tiles: empty chunks
     (1, 1, 8, 640, 64, False, 1.0, 1, False),         # splits = 1
+    # more than 128 and more than 192 entries in one workgroup's walk: the window of entry starts
+    # that a wavefront keeps in registers moves on once and twice
+    (1, 1, 40, 9000, 128, False, 0.5, 1, True),
+    (1, 1, 40, 9000, 64, True, 0.5, 1, False),
+    (1, 1, 8, 13000, 128, False, 0.5, 1, True),
+    (1, 1, 8, 13000, 32, True, 0.5, 2, False),
 ]
 
 
