@@ -3,8 +3,9 @@
 // One workgroup per block row of the layout (block_m = 32 * NW queries, one wavefront per 32
 // queries).  The workgroup walks only the stored tiles of its block row.  Per tile:
 //   1. the 64 key rows and 64 value rows go from HBM/L2 straight into LDS with 128-bit
-//      buffer loads that write LDS directly (no staging registers); the next tile's loads are
-//      issued before the current tile is computed (two LDS stages) so they fly under the math;
+//      buffer loads that write LDS directly (no staging registers); the loads of the next tile
+//      (two LDS stages), or of the next tile's keys and this tile's values (one stage: half the
+//      LDS, more workgroups per compute unit), are in flight while the current tile is computed;
 //      LDS rows are unpadded and XOR-swizzled in 16-byte chunks so that both the key-operand
 //      reads and the transposing value reads are bank-conflict free;
 //   2. S^T = K Q^T on v_mfma_f32_32x32x16_bf16, so that every lane holds scores of ONE query
