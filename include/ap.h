@@ -115,7 +115,8 @@ ap_status ap_build_layout_cropped(const uint8_t *mask, int H, int Lq_stored, int
  *
  * A mask that keeps a band next to the diagonal (the constant context window that the figure of
  * Section 5.1 shows for self-attention) plus scattered isolated connections has a kept entry in
- * nearly every tile of a long sequence, although few tiles hold many.  The schedule lists, per block row, "entries" of 64 keys each: a stored tile whose visible part
+ * nearly every tile of a long sequence, although few tiles hold many.  The schedule lists, per
+ * block row, "entries" of 64 keys each: a stored tile whose visible part
  * spans at least `min_cols` distinct key columns stays a run of 64 consecutive keys; the visible
  * columns of all other tiles of the block row are packed, ascending, into gathered entries of 64
  * arbitrary keys.  The causal limit (if any) is folded into the entry bitmaps, so a schedule must
@@ -253,8 +254,12 @@ ap_status ap_sparse_attn_decode(const void *Q, const void *K, const void *V, voi
  *     O[b,h,i,:] = sum_j p_ij V[b,h,j,:]
  *
  * (the optimality conditions of 1.5-entmax; many p_ij are exactly 0).  tau is found by Newton's
- * iteration to |sum_j p_ij - 1| <= 1e-5 and O is divided by the attained sum.  A query with no
- * visible kept key gets O = 0 and tau = +infinity.
+ * iteration, which rises monotonically to the root: a row stops when |sum_j p_ij - 1| <= 1e-5 at
+ * its tau, or after the one further step taken from a tau with |sum_j p_ij - 1| <= 1e-2 (the
+ * steps converge quadratically, so the returned tau leaves |sum_j p_ij - 1| <= 1e-4).  O is
+ * divided by the attained sum, so its weights sum to one whatever the residual; the backward call
+ * forms p from the returned tau without that division.  A query with no visible kept key gets
+ * O = 0 and tau = +infinity.
  *
  *   tau           out, float [B, H, Lq] contiguous, or NULL
  *   everything else as in ap_sparse_attn_fwd; a block row with more than 64 schedule entries
@@ -470,8 +475,10 @@ ap_status ap_accumulate_attention_maps_lse(const void *Q, const void *K, const f
  *   workspace     device scratch of at least ap_prune_mask_workspace_bytes() bytes, 16-byte
  *                 aligned; contents undefined before and after
  *
- * Exact: tau is an element of abar, found by a three-pass radix selection over the bit
- * patterns; integer atomics only, so the result is bit-identical from run to run.
+ * Exact: tau is an element of abar, found by radix selection over the bit patterns in two sweeps
+ * over the map (a histogram of the leading key bits, then the candidates of the selected interval;
+ * more histogram levels only when that interval holds a very large number of ties); integer
+ * atomics only, so the result is bit-identical from run to run.
  * ------------------------------------------------------------------------------------------- */
 size_t ap_prune_mask_workspace_bytes(void);
 

@@ -256,6 +256,24 @@ def ap_build_schedule(layout: Layout, causal: bool = False, min_cols: int = 0,
     return sched
 
 
+def _check_out(out: torch.Tensor, like: torch.Tensor, name: str = "out"):
+    """A caller-supplied output must be what the kernels will write: like's shape, dtype and
+    device, last dimension contiguous (the C ABI sees only a pointer and three strides)."""
+    if tuple(out.shape) != tuple(like.shape) or out.dtype != like.dtype or out.device != like.device:
+        raise ValueError("%s must be a %s tensor of shape %s on %s" % (
+            name, like.dtype, tuple(like.shape), like.device))
+    if out.stride(3) != 1:
+        raise ValueError("%s: last dimension must be contiguous" % name)
+
+
+def _check_rows_f32(t: torch.Tensor, like: torch.Tensor, name: str):
+    """Per-query statistics (lse, tau): contiguous float32 [B, H, Lq] on like's device."""
+    if t.dtype != torch.float32 or tuple(t.shape) != tuple(like.shape[:3]) or t.device != like.device \
+            or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous float32 tensor of shape %s on %s" % (
+            name, tuple(like.shape[:3]), like.device))
+
+
 def _strides3(t: torch.Tensor):
     return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
 
@@ -293,8 +311,12 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
     cs = sched.c_struct() if sched is not None else None
     if out is None:
         out = torch.empty((B, H, Lq, D), dtype=Q.dtype, device=Q.device)
+    else:
+        _check_out(out, Q)
     if lse is None and return_lse:
         lse = torch.empty((B, H, Lq), dtype=torch.float32, device=Q.device)
+    elif lse is not None:
+        _check_rows_f32(lse, Q, "lse")
     st = lib().ap_sparse_attn_fwd(
         Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
         lse.data_ptr() if lse is not None else None, dt, B, H, Lq, Lk, D,
@@ -326,6 +348,8 @@ def ap_sparse_attn_decode(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, lay
             raise ValueError("last dimension must be contiguous")
     if out is None:
         out = torch.empty((B, H, Lq, D), dtype=Q.dtype, device=Q.device)
+    else:
+        _check_out(out, Q)
     lse = torch.empty((B, H, Lq), dtype=torch.float32, device=Q.device) if return_lse else None
     ws_bytes = ap_fwd_split_workspace_bytes(B, H, Lq, D, splits) if splits > 1 else 0
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=Q.device)
@@ -360,6 +384,8 @@ def ap_sparse_attn_entmax15_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tenso
         raise ValueError("layout was built for other sizes")
     if out is None:
         out = torch.empty((B, H, Lq, D), dtype=Q.dtype, device=Q.device)
+    else:
+        _check_out(out, Q)
     tau = torch.empty((B, H, Lq), dtype=torch.float32, device=Q.device) if return_tau else None
     st = lib().ap_sparse_attn_entmax15_fwd(
         Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
@@ -397,6 +423,8 @@ def ap_sparse_attn_fwd_split(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, 
     cs = sched.c_struct() if sched is not None else None
     if out is None:
         out = torch.empty((B, H, Lq, D), dtype=Q.dtype, device=Q.device)
+    else:
+        _check_out(out, Q)
     lse = torch.empty((B, H, Lq), dtype=torch.float32, device=Q.device) if return_lse else None
     ws_bytes = ap_fwd_split_workspace_bytes(B, H, Lq, D, splits)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=Q.device)
@@ -489,6 +517,7 @@ def ap_sparse_attn_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, O: tor
         if dO.stride() != O.stride():
             raise ValueError("dO must have O's strides")
     lse = lse.contiguous()
+    _check_rows_f32(lse, Q, "lse")
     dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
     dK = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device)
     dV = torch.empty_strided(V.shape, V.stride(), dtype=V.dtype, device=V.device)
@@ -537,6 +566,7 @@ def ap_sparse_attn_entmax15_bwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tenso
         if sc.causal != bool(causal):
             raise ValueError("schedule was built with another `causal`")
     tau = tau.contiguous()
+    _check_rows_f32(tau, Q, "tau")
     dQ = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
     dK = torch.empty_strided(K.shape, K.stride(), dtype=K.dtype, device=K.device)
     dV = torch.empty_strided(V.shape, V.stride(), dtype=V.dtype, device=V.device)

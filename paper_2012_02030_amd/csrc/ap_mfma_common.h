@@ -57,6 +57,7 @@ __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" 
 // written as inline assembly on purpose: the compiler then does not know that LDS is being
 // written asynchronously, so it does not make every later LDS read wait for all loads in
 // flight; completion is enforced by wait_vmem() and the workgroup barrier in the main loop.
+// M0 is listed as clobbered so that no value of the compiler's own is assumed to survive in it.
 typedef __attribute__((ext_vector_type(4))) int rsrc_t;
 __device__ __forceinline__ void load16_to_lds(unsigned lds_addr, int voff, rsrc_t rsrc, int soff)
 {
@@ -69,7 +70,7 @@ __device__ __forceinline__ void load16_to_lds(unsigned lds_addr, int voff, rsrc_
     soff = __builtin_amdgcn_readfirstlane(soff);
     lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 
 // Raw buffer descriptor: base address, stride 0, num_records bytes; loads beyond num_records

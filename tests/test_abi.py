@@ -385,6 +385,35 @@ def test_decode_arguments(L):
     assert dec(causal=1, Lq=128, Lk=64) == ap.AP_ERR_INVALID_ARG
 
 
+def test_binding_rejects_caller_supplied_outputs_that_do_not_fit():
+    """The C ABI sees only pointers: the binding checks shape, dtype, device and layout of `out`,
+    `lse` and `tau` before anything reaches the library (host tensors suffice to show it)."""
+    import torch
+
+    B, H, Lq, Lk, D = 2, 2, 64, 64, 32
+    q = torch.zeros((B, H, Lq, D), dtype=torch.bfloat16)
+    k = torch.zeros((B, H, Lk, D), dtype=torch.bfloat16)
+    z32 = torch.zeros(1, dtype=torch.int32)
+    lay = ap.Layout(z32, z32, torch.zeros((1, 64, 1), dtype=torch.int64), torch.zeros(1, dtype=torch.int64),
+                    H, Lq, Lk, 64, 64)
+    bad_outs = [torch.zeros((B, H, Lq, D), dtype=torch.float32),          # dtype
+                torch.zeros((B, H, Lq + 1, D), dtype=torch.bfloat16),     # shape
+                torch.zeros((B, H, D, Lq), dtype=torch.bfloat16).transpose(2, 3)]   # last stride
+    for out in bad_outs:
+        for call in (lambda: ap.ap_sparse_attn_fwd(q, k, k, lay, out=out),
+                     lambda: ap.ap_sparse_attn_fwd_split(q, k, k, lay, 2, out=out),
+                     lambda: ap.ap_sparse_attn_decode(q, k, k, lay, out=out),
+                     lambda: ap.ap_sparse_attn_entmax15_fwd(q, k, k, lay, out=out)):
+            with pytest.raises(ValueError):
+                call()
+    bad_lses = [torch.zeros((B, H, Lq), dtype=torch.float64),
+                torch.zeros((B, H, Lq + 1), dtype=torch.float32),
+                torch.zeros((B, Lq, H), dtype=torch.float32).transpose(1, 2)]
+    for lse in bad_lses:
+        with pytest.raises(ValueError):
+            ap.ap_sparse_attn_fwd(q, k, k, lay, lse=lse)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(ap, "_lib", None)
     monkeypatch.setattr(ap, "LIB_PATH", "/nonexistent/libap_mi355x.so")

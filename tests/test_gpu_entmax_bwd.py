@@ -2,8 +2,9 @@
 against the fp64 oracle.
 
 Tolerance: as for the softmax backward pass (P, dS and the results are rounded to bf16; the bar is
-max-abs error <= 2e-2 * max(1, max|oracle gradient|)).  The forward pass's tau is exact to
-|sum p - 1| <= 1e-5, far below that.
+max-abs error <= 2e-2 * max(1, max|oracle gradient|), per tensor and per row).  The forward
+pass's tau leaves |sum p - 1| <= 1e-4 (tests/test_gpu_entmax.py), and the backward pass forms
+p = u^2 from it without renormalising: far below that bar.
 """
 import numpy as np
 import pytest
@@ -13,7 +14,7 @@ import oracle
 from paper_2012_02030_amd import binding as ap
 from paper_2012_02030_amd import synth
 
-from gpu_util import to_device
+from gpu_util import assert_grad_close, to_device
 from test_gpu_bwd import BWD_CASES, rand_inputs
 
 pytestmark = pytest.mark.gpu
@@ -34,11 +35,7 @@ def run_entmax_bwd(Q, K, V, dO, mask_np, causal, scale=0.0, min_cols=0, min_rows
     torch.cuda.synchronize()
     ref = oracle.masked_entmax15_attention_backward(rq, rk, rv, mask_np, rg, causal=causal, scale=scale)
     for name, got, want in zip(("dQ", "dK", "dV"), got3, ref):
-        g = got.double().cpu().numpy()
-        assert np.isfinite(g).all(), name + " has non-finite entries"
-        tol = 2e-2 * max(1.0, float(np.abs(want).max()))
-        err = float(np.abs(g - want).max())
-        assert err <= tol, "max |%s - oracle| = %.3e > %.3e" % (name, err, tol)
+        assert_grad_close(name, got.double().cpu().numpy(), want)
 
 
 @pytest.mark.parametrize("case", BWD_CASES, ids=lambda c: "B%d_H%d_%dx%d_D%d_%s_%g" % (c[:5] + ("causal" if c[5] else "full", c[6])))
@@ -85,6 +82,4 @@ def test_entmax_backward_full_size_c5_one_slice_against_oracle():
     sl = lambda t: t[b:b + 1, h:h + 1].double().cpu().numpy()
     ref = oracle.masked_entmax15_attention_backward(sl(dq), sl(dk), sl(dv), mask[h:h + 1], sl(dg), causal=True)
     for name, got, want in zip(("dQ", "dK", "dV"), (gQ, gK, gV), ref):
-        err = float(np.abs(sl(got) - want).max())
-        tol = 2e-2 * max(1.0, float(np.abs(want).max()))
-        assert err <= tol, "%s[%d,%d]: %.3e > %.3e" % (name, b, h, err, tol)
+        print("C5 entmax bwd", name, assert_grad_close(name, sl(got), want, "[%d,%d]" % (b, h)), flush=True)
