@@ -66,7 +66,7 @@ GRAD_TOL = 2e-2        # gradient error allowed per unit of max(1, largest oracl
 GRAD_REL_FRO = 1e-2    # ||got - oracle||_F / ||oracle||_F allowed per tensor
 
 
-def assert_grad_close(name, got: np.ndarray, want: np.ndarray, where=""):
+def assert_grad_close(name, got: np.ndarray, want: np.ndarray, where="", per_row=True):
     """Gradient parity bar, three checks on one [..., L, D] tensor against the fp64 oracle:
     every row (one query of dQ, one key of dK or dV) within GRAD_TOL * max(1, max|oracle row|),
     the whole tensor within GRAD_TOL * max(1, max|oracle|) (implied by the rows; kept as the
@@ -74,7 +74,10 @@ def assert_grad_close(name, got: np.ndarray, want: np.ndarray, where=""):
     per-row scale follows from where the rounding happens: P, dS and the stored result are
     rounded to bf16, i.e. relative to their own magnitude, and a row's entries are sums over the
     same set of partners, so a row's error scales with that row's entries, not with the largest
-    entry of some other row.  Returns (max error, worst row ratio, relative Frobenius error)."""
+    entry of some other row.  per_row=False drops the row check: only for inputs built so that
+    dS = P (dP - delta) cancels (nearly one-hot P), where a row's error is set by the rounding of
+    delta = <dO, O> from the bf16 O, i.e. by |dO_i| |O_i| and not by the row's own, much smaller
+    entries.  Returns (max error, worst row ratio, relative Frobenius error)."""
     assert np.isfinite(got).all(), "%s%s has non-finite entries" % (name, where)
     diff = np.abs(got - want)
     err = float(diff.max())
@@ -83,7 +86,7 @@ def assert_grad_close(name, got: np.ndarray, want: np.ndarray, where=""):
     row_tol = GRAD_TOL * np.maximum(1.0, np.abs(want).max(axis=-1))
     ratio = diff.max(axis=-1) / row_tol
     worst = float(ratio.max())
-    assert worst <= 1.0, "%s%s: row %s off by %.3e against a row bound of %.3e" % (
+    assert worst <= 1.0 or not per_row, "%s%s: row %s off by %.3e against a row bound of %.3e" % (
         name, where, np.unravel_index(int(ratio.argmax()), ratio.shape),
         float(diff.max(axis=-1).flat[int(ratio.argmax())]), float(row_tol.flat[int(ratio.argmax())]))
     norm = float(np.sqrt((want * want).sum()))

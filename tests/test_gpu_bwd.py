@@ -53,7 +53,7 @@ def test_layout_transpose_matches_definition(shape):
     assert np.array_equal(lt.tile_idx[:nnz].cpu().numpy(), tile_idx)
 
 
-def run_bwd(Q, K, V, dO, mask_np, causal, scale=0.0):
+def run_bwd(Q, K, V, dO, mask_np, causal, scale=0.0, per_row=True):
     dq, rq = to_device(Q, "bf16")
     dk, rk = to_device(K, "bf16")
     dv, rv = to_device(V, "bf16")
@@ -66,7 +66,7 @@ def run_bwd(Q, K, V, dO, mask_np, causal, scale=0.0):
     ref = oracle.masked_attention_backward(rq, rk, rv, mask_np, rg, causal=causal, scale=scale)
     errs = []
     for name, got, want in zip(("dQ", "dK", "dV"), (gQ, gK, gV), ref):
-        errs.append(assert_grad_close(name, got.double().cpu().numpy(), want)[0])
+        errs.append(assert_grad_close(name, got.double().cpu().numpy(), want, per_row=per_row)[0])
     return errs
 
 
@@ -106,9 +106,14 @@ def test_backward_on_the_structured_masks():
 
 
 def test_backward_explicit_scale_and_large_scores():
+    """Scores with a standard deviation of 6.4: P is nearly one-hot, so dS = P (dP - delta) is a
+    difference of two numbers of size |dO_i| |V_j| ~ 8 that nearly cancel.  delta comes from the
+    forward pass's bf16 O (8 * 2^-9 ~ 0.02 absolute), which then sets the error of a row whose own
+    entries are far smaller: the row-scaled check does not apply here, the tensor-wide bound and the
+    Frobenius bound do."""
     Q, K, V, dO = rand_inputs(9, 1, 2, 128, 128, 64)
     mask = synth.random_mask(2, 128, 128, 0.4, seed=3)
-    run_bwd(2.0 * Q, 2.0 * K, V, dO, mask, False, scale=0.2)
+    run_bwd(2.0 * Q, 2.0 * K, V, dO, mask, False, scale=0.2, per_row=False)
 
 
 def test_backward_full_size_c5_two_slices_against_oracle():
