@@ -216,6 +216,35 @@ ap_status ap_sparse_attn_fwd_split(const void *Q, const void *K, const void *V, 
                                    int splits, void *workspace, size_t workspace_bytes,
                                    void *stream);
 
+/*
+ * ap_sparse_attn_fwd_split for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments without the workspace, same kernels, same result bit for bit.  The partial outputs
+ * live in a device array that is part of the library's code object (each GPU the library runs on
+ * holds AP_FWD_SPLIT_STATIC_MAX_BYTES of it until the process ends); the call allocates and frees
+ * nothing and calls no allocating routine.
+ *
+ *   - ap_fwd_split_workspace_bytes(B, H, Lq, D, splits) must not exceed
+ *     AP_FWD_SPLIT_STATIC_MAX_BYTES, else AP_ERR_CAPACITY (checked on the host, before anything
+ *     else happens).
+ *   - The first call on a device looks up that device's copy of the array (one runtime query, no
+ *     allocation); make that first call outside graph capture.
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (two
+ *     streams, two host threads) race; serialise them.  Nothing in the array has to start at
+ *     zero (every chunk writes its whole partial result before the merge reads it), so the call
+ *     clears nothing and the previous call's contents are simply overwritten.
+ */
+#define AP_FWD_SPLIT_STATIC_MAX_BYTES ((size_t)32 << 20)
+
+ap_status ap_sparse_attn_fwd_split_static(const void *Q, const void *K, const void *V, void *O, float *lse,
+                                          ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                          const int64_t *stride_q, const int64_t *stride_k,
+                                          const int64_t *stride_v, const int64_t *stride_o,
+                                          const int32_t *row_ptr, const int32_t *col_idx,
+                                          const uint64_t *bitmaps, int block_m, int block_n,
+                                          const ap_schedule *sched, int causal, float softmax_scale,
+                                          int splits, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Masked attention forward for one or a few queries against many keys (the limit of the
  * cached-memory setting of Section 4.1: a new position attends to everything stored before it under

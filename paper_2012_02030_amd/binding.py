@@ -27,7 +27,7 @@ AP_BF16 = 1
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
            "ap_build_layout", "ap_build_layout_cropped", "ap_build_schedule", "ap_sparse_attn_fwd",
            "ap_sparse_attn_entmax15_fwd", "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
-           "ap_sparse_attn_decode",
+           "ap_sparse_attn_fwd_split_static", "ap_sparse_attn_decode",
            "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
            "ap_build_col_schedule", "ap_sparse_attn_bwd_sched",
            "ap_entmax15_bwd_workspace_bytes", "ap_sparse_attn_entmax15_bwd",
@@ -102,6 +102,12 @@ def lib() -> ctypes.CDLL:
                                                ctypes.POINTER(i64), ctypes.POINTER(i64),
                                                vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
                                                ctypes.c_float, i32, vp, ctypes.c_size_t, vp]
+        L.ap_sparse_attn_fwd_split_static.restype = i32
+        L.ap_sparse_attn_fwd_split_static.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                                      ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                                      ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                                      vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
+                                                      ctypes.c_float, i32, vp]
         L.ap_build_layout_transpose.restype = i32
         L.ap_build_layout_transpose.argtypes = [vp, vp, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
         L.ap_bwd_workspace_bytes.restype = ctypes.c_size_t
@@ -438,6 +444,43 @@ def ap_sparse_attn_fwd_split(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, 
         _stream_ptr(stream))
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_fwd_split")
+    return out, lse
+
+
+AP_FWD_SPLIT_STATIC_MAX_BYTES = 32 << 20
+
+
+def ap_sparse_attn_fwd_split_static(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout: Layout,
+                                    splits: int, out: torch.Tensor, lse: Optional[torch.Tensor] = None,
+                                    causal: bool = False, softmax_scale: float = 0.0,
+                                    stream: Optional[torch.cuda.Stream] = None,
+                                    sched: Optional[Schedule] = None):
+    """ap_sparse_attn_fwd_split without a workspace: the partial results live in the library's own
+    device array.  Nothing is allocated here either, so the caller passes `out` (and `lse`, or
+    None to skip it).  Calls that may overlap on one GPU race; serialise them."""
+    if Q.dtype != torch.bfloat16 or K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise ValueError("Q, K, V must be bfloat16")
+    B, H, Lq, D = Q.shape
+    Lk = K.shape[2]
+    if tuple(K.shape) != (B, H, Lk, D) or tuple(V.shape) != (B, H, Lk, D):
+        raise ValueError("K/V shape mismatch")
+    if (H, Lq, Lk) != (layout.H, layout.Lq, layout.Lk):
+        raise ValueError("layout was built for other sizes")
+    if sched is not None and sched.causal != bool(causal):
+        raise ValueError("schedule was built with causal=%s" % sched.causal)
+    _check_out(out, Q)
+    if lse is not None:
+        _check_rows_f32(lse, Q, "lse")
+    cs = sched.c_struct() if sched is not None else None
+    st = lib().ap_sparse_attn_fwd_split_static(
+        Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+        lse.data_ptr() if lse is not None else None, AP_BF16, B, H, Lq, Lk, D,
+        _strides3(Q), _strides3(K), _strides3(V), _strides3(out),
+        layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
+        layout.block_m, layout.block_n, ctypes.byref(cs) if cs is not None else None,
+        int(bool(causal)), float(softmax_scale), int(splits), _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_sparse_attn_fwd_split_static")
     return out, lse
 
 

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 #include <initializer_list>
 #include <math.h>
+#include <mutex>
 #include <stdint.h>
 
 #include "ap.h"
@@ -10,6 +11,29 @@
 namespace {
 
 inline bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// Scratch of ap_sparse_attn_fwd_split_static: partial outputs and their log-sum-exp.  Part of the
+// code object, so every GPU that loads the library holds its own copy at its own address.  In
+// host code the name is only a handle for hipGetSymbolAddress; the kernels get the address.
+static __device__ __align__(256) unsigned char scratch[AP_FWD_SPLIT_STATIC_MAX_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};      // per device, resolved on the first call there
+
+// Address of the current device's copy of `scratch` (null on failure).
+void* static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
 
 bool strides_ok(const int64_t* s, int D, int elems_per_16b)
 {
@@ -264,6 +288,27 @@ ap_status ap_sparse_attn_fwd_split(const void* Q, const void* K, const void* V, 
     return fwd_common(Q, K, V, O, lse, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v, stride_o,
                       row_ptr, col_idx, bitmaps, block_m, block_n, sched, causal, softmax_scale, splits,
                       workspace, workspace_bytes, stream);
+}
+
+ap_status ap_sparse_attn_fwd_split_static(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                          ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                          const int64_t* stride_q, const int64_t* stride_k,
+                                          const int64_t* stride_v, const int64_t* stride_o,
+                                          const int32_t* row_ptr, const int32_t* col_idx,
+                                          const uint64_t* bitmaps, int block_m, int block_n,
+                                          const ap_schedule* sched, int causal, float softmax_scale,
+                                          int splits, void* stream)
+{
+    if (splits <= 0 || B <= 0 || H <= 0 || Lq <= 0 || D <= 0) return AP_ERR_INVALID_ARG;
+    // the size check comes first and needs no GPU: 128-bit arithmetic cannot wrap for int arguments
+    const unsigned __int128 need = (unsigned __int128)splits * (unsigned)B * (unsigned)H * (unsigned)Lq *
+                                   ((unsigned)D + 1u) * sizeof(float);
+    if (need > (unsigned __int128)AP_FWD_SPLIT_STATIC_MAX_BYTES) return AP_ERR_CAPACITY;
+    void* ws = static_scratch();
+    if (!ws) return AP_ERR_HIP;
+    return fwd_common(Q, K, V, O, lse, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v, stride_o,
+                      row_ptr, col_idx, bitmaps, block_m, block_n, sched, causal, softmax_scale, splits,
+                      ws, AP_FWD_SPLIT_STATIC_MAX_BYTES, stream);
 }
 
 ap_status ap_build_layout_transpose(const int32_t* row_ptr, const int32_t* col_idx, int H, int Lq,

@@ -205,6 +205,26 @@ def test_split_forward_arguments(L):
     assert call(sq=bad) == ap.AP_ERR_INVALID_ARG
 
 
+def test_static_split_forward_rejects_sizes_beyond_its_array(L):
+    """The allocation-free variant checks its fixed capacity on the host before anything else."""
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+
+    def call(B, H, Lq, D, splits):
+        return L.ap_sparse_attn_fwd_split_static(fake, fake + 0x100000, fake + 0x200000, fake + 0x300000, None,
+                                                 ap.AP_BF16, B, H, Lq, 64, D, s, s, s, s, fake, fake, fake,
+                                                 64, 64, None, 0, 0.0, splits, None)
+
+    assert call(1, 2, 64, 64, 0) == ap.AP_ERR_INVALID_ARG
+    assert call(0, 2, 64, 64, 4) == ap.AP_ERR_INVALID_ARG
+    limit = ap.AP_FWD_SPLIT_STATIC_MAX_BYTES
+    assert ap.ap_fwd_split_workspace_bytes(4, 16, 64, 128, 16) > limit
+    assert call(4, 16, 64, 128, 16) == ap.AP_ERR_CAPACITY
+    assert call(65535, 65535, 1 << 30, 128, 1024) == ap.AP_ERR_CAPACITY       # no wrap-around
+    text = open(os.path.join(ROOT, "include", "ap.h")).read()
+    assert "#define AP_FWD_SPLIT_STATIC_MAX_BYTES ((size_t)32 << 20)" in text and limit == 32 << 20
+
+
 def test_entmax_forward_arguments(L):
     fake = 0x1000
     s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
