@@ -118,8 +118,9 @@ ap_status ap_build_layout_cropped(const uint8_t *mask, int H, int Lq_stored, int
  * nearly every tile of a long sequence, although few tiles hold many.  The schedule lists, per
  * block row, "entries" of 64 keys each: a stored tile whose visible part
  * spans at least `min_cols` distinct key columns stays a run of 64 consecutive keys; the visible
- * columns of all other tiles of the block row are packed, ascending, into gathered entries of 64
- * arbitrary keys.  The causal limit (if any) is folded into the entry bitmaps, so a schedule must
+ * columns of all other tiles of the block row are packed into gathered entries of 64 arbitrary,
+ * distinct keys (grouped by which 32-query groups of the block row use a column, so that most
+ * gathered entries concern one group only; the order inside an entry carries no meaning).  The causal limit (if any) is folded into the entry bitmaps, so a schedule must
  * be used with the same `causal` flag and the same layout it was built from.  It is a pure
  * function of its inputs (fixed order, no atomics) and never changes which (query, key) pairs
  * are evaluated -- only how they are grouped.
