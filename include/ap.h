@@ -110,6 +110,25 @@ ap_status ap_build_layout_cropped(const uint8_t *mask, int H, int Lq_stored, int
                                   uint64_t *bitmaps, int64_t cap, int64_t *nnz_out, void *workspace,
                                   size_t workspace_bytes, void *stream);
 
+/*
+ * The layout straight from the mean attention map (Section 3.2, Eq. (2)): the strict comparison
+ * with the layer's threshold is evaluated inside the scan, so the byte mask is never written or
+ * read.  The result is bit for bit the layout that ap_build_layout produces for the mask that
+ * ap_prune_mask writes for the same map and threshold:
+ *
+ *     kept(h,i,j)  <=>  not (abar[h,i,j] < tau)  and  (not causal or j <= i + (Lk - Lq))
+ *
+ *   abar          float [H, Lq, Lk] contiguous (as for ap_prune_mask; entries that causality hides
+ *                 may hold anything, they are never kept)
+ *   tau           device pointer to the threshold, e.g. ap_prune_mask's tau_out (that call
+ *                 accepts mask = NULL to compute the threshold only); +infinity keeps nothing
+ *   everything else as in ap_build_layout, workspace included; block_n must be 64
+ */
+ap_status ap_build_layout_from_map(const float *abar, const float *tau, int H, int Lq, int Lk, int causal,
+                                   int block_m, int block_n, int32_t *row_ptr, int32_t *col_idx,
+                                   uint64_t *bitmaps, int64_t cap, int64_t *nnz_out, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Visit schedule: an optional, derived re-packing of a layout for the attention kernel.
  *
@@ -500,7 +519,8 @@ ap_status ap_accumulate_attention_maps_lse(const void *Q, const void *K, const f
  *   abar          float [H, Lq, Lk] contiguous, 16-byte aligned; values must be >= 0 and not
  *                 NaN (they are means of probabilities)
  *   prune_fraction  p of the paper as a fraction, 0 <= p <= 1
- *   mask          out, uint8 [H, Lq, Lk] contiguous
+ *   mask          out, uint8 [H, Lq, Lk] contiguous; or NULL to compute the threshold only (then
+ *                 tau_out is required; ap_build_layout_from_map takes it from there)
  *   tau_out       out, one float (device), or NULL
  *   workspace     device scratch of at least ap_prune_mask_workspace_bytes() bytes, 16-byte
  *                 aligned; contents undefined before and after

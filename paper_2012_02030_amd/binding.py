@@ -25,7 +25,7 @@ AP_F32 = 0
 AP_BF16 = 1
 
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
-           "ap_build_layout", "ap_build_layout_cropped", "ap_build_schedule", "ap_sparse_attn_fwd",
+           "ap_build_layout", "ap_build_layout_cropped", "ap_build_layout_from_map", "ap_build_schedule", "ap_sparse_attn_fwd",
            "ap_sparse_attn_entmax15_fwd", "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
            "ap_sparse_attn_fwd_split_static", "ap_sparse_attn_decode",
            "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
@@ -73,6 +73,9 @@ def lib() -> ctypes.CDLL:
         L.ap_build_layout_cropped.restype = i32
         L.ap_build_layout_cropped.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp,
                                               ctypes.c_size_t, vp]
+        L.ap_build_layout_from_map.restype = i32
+        L.ap_build_layout_from_map.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, i64, vp, vp,
+                                               ctypes.c_size_t, vp]
         L.ap_build_schedule.restype = i32
         L.ap_build_schedule.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i64, i32, i32,
                                         ctypes.POINTER(_CSchedule), vp]
@@ -224,6 +227,41 @@ def ap_build_layout(mask: torch.Tensor, block_m: int = 64, block_n: int = 64,
         raise ApError(st, "ap_build_layout")
     # ws is released to torch's caching allocator here; the allocator is stream-ordered, so the
     # kernels enqueued above finish with it before any later allocation on this stream reuses it
+    return Layout(row_ptr, col_idx, bitmaps, nnz, H, Lq, Lk, block_m, block_n)
+
+
+def ap_build_layout_from_map(abar: torch.Tensor, tau: torch.Tensor, causal: bool = False, block_m: int = 64,
+                             block_n: int = 64, cap: Optional[int] = None,
+                             stream: Optional[torch.cuda.Stream] = None) -> Layout:
+    """Layout of the mask {not (abar < tau), and visible if causal} without writing that mask.
+
+    abar: float32 device tensor [H, Lq, Lk]; tau: float32 device tensor with one element (e.g. the
+    second result of ap_prune_mask).  Asynchronous on the stream."""
+    if abar.dtype != torch.float32 or abar.dim() != 3 or not abar.is_cuda:
+        raise ValueError("abar must be a float32 device tensor [H, Lq, Lk]")
+    if tau.dtype != torch.float32 or tau.numel() != 1 or tau.device != abar.device:
+        raise ValueError("tau must be a float32 tensor with one element on abar's device")
+    abar = abar.contiguous()
+    H, Lq, Lk = abar.shape
+    max_tiles = ap_layout_max_tiles(H, Lq, Lk, block_m, block_n)
+    if max_tiles < 0:
+        raise ApError(AP_ERR_UNSUPPORTED, "ap_layout_max_tiles")
+    if cap is None:
+        cap = max_tiles
+    dev = abar.device
+    nqb = -(-Lq // block_m)
+    W = -(-block_n // 64)
+    row_ptr = torch.empty(H * nqb + 1, dtype=torch.int32, device=dev)
+    nnz = torch.empty(1, dtype=torch.int64, device=dev)
+    ws_bytes = ap_layout_workspace_bytes(H, Lq, Lk, block_m, block_n)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    col_idx = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+    bitmaps = torch.empty((max(cap, 1), block_m, W), dtype=torch.int64, device=dev)
+    st = lib().ap_build_layout_from_map(abar.data_ptr(), tau.data_ptr(), H, Lq, Lk, int(bool(causal)), block_m,
+                                        block_n, row_ptr.data_ptr(), col_idx.data_ptr(), bitmaps.data_ptr(), cap,
+                                        nnz.data_ptr(), ws.data_ptr(), ws_bytes, _stream_ptr(stream))
+    if st != AP_OK:
+        raise ApError(st, "ap_build_layout_from_map")
     return Layout(row_ptr, col_idx, bitmaps, nnz, H, Lq, Lk, block_m, block_n)
 
 
@@ -677,20 +715,21 @@ def ap_prune_mask_workspace_bytes() -> int:
 
 
 def ap_prune_mask(abar: torch.Tensor, prune_fraction: float, causal: bool = False,
-                  stream: Optional[torch.cuda.Stream] = None):
+                  stream: Optional[torch.cuda.Stream] = None, threshold_only: bool = False):
     """abar: float32 device tensor [H, Lq, Lk], the mean maps of all heads of one layer.
 
-    Returns (mask uint8 [H,Lq,Lk] with 1 = kept, tau float32 [1] on device).  Asynchronous."""
+    Returns (mask uint8 [H,Lq,Lk] with 1 = kept, tau float32 [1] on device); with threshold_only the
+    mask is not written and None is returned in its place.  Asynchronous."""
     if abar.dtype != torch.float32 or abar.dim() != 3 or not abar.is_cuda:
         raise ValueError("abar must be a float32 device tensor [H, Lq, Lk]")
     abar = abar.contiguous()
     H, Lq, Lk = abar.shape
-    mask = torch.empty((H, Lq, Lk), dtype=torch.uint8, device=abar.device)
+    mask = None if threshold_only else torch.empty((H, Lq, Lk), dtype=torch.uint8, device=abar.device)
     tau = torch.empty(1, dtype=torch.float32, device=abar.device)
     ws_bytes = ap_prune_mask_workspace_bytes()
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=abar.device)
     st = lib().ap_prune_mask(abar.data_ptr(), H, Lq, Lk, int(bool(causal)), float(prune_fraction),
-                             mask.data_ptr(), tau.data_ptr(), ws.data_ptr(), ws_bytes,
+                             mask.data_ptr() if mask is not None else None, tau.data_ptr(), ws.data_ptr(), ws_bytes,
                              _stream_ptr(stream))
     if st != AP_OK:
         raise ApError(st, "ap_prune_mask")

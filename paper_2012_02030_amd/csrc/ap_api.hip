@@ -112,6 +112,28 @@ ap_status ap_build_layout_cropped(const uint8_t* mask, int H, int Lq_stored, int
                                row_ptr, col_idx, bitmaps, cap, nnz_out, workspace, workspace_bytes, stream);
 }
 
+ap_status ap_build_layout_from_map(const float* abar, const float* tau, int H, int Lq, int Lk, int causal,
+                                   int block_m, int block_n, int32_t* row_ptr, int32_t* col_idx,
+                                   uint64_t* bitmaps, int64_t cap, int64_t* nnz_out, void* workspace,
+                                   size_t workspace_bytes, void* stream)
+{
+    if (H <= 0 || Lq <= 0 || Lk <= 0 || block_m <= 0 || block_n <= 0) return AP_ERR_INVALID_ARG;
+    if (!ap::layout_shape_ok(H, Lq, Lk, block_m, block_n)) return AP_ERR_UNSUPPORTED;
+    if (block_n != 64) return AP_ERR_UNSUPPORTED;            // the attention kernels' window width
+    if (!abar || !tau || !row_ptr || !workspace) return AP_ERR_INVALID_ARG;
+    if (causal && Lk < Lq) return AP_ERR_INVALID_ARG;
+    if ((col_idx == nullptr) != (bitmaps == nullptr)) return AP_ERR_INVALID_ARG;
+    if (col_idx && cap < 0) return AP_ERR_INVALID_ARG;
+    if (!aligned(abar, 4) || !aligned(tau, 4) || !aligned(row_ptr, 4) || !aligned(col_idx, 4) ||
+        !aligned(bitmaps, 8) || !aligned(nnz_out, 8) || !aligned(workspace, 8))
+        return AP_ERR_INVALID_ARG;
+    if (workspace_bytes < ap_layout_workspace_bytes(H, Lq, Lk, block_m, block_n)) return AP_ERR_CAPACITY;
+    const hipError_t e = ap::launch_build_layout_from_map(abar, tau, causal ? 1 : 0, H, Lq, Lk, block_m, block_n,
+                                                          row_ptr, col_idx, bitmaps, (long long)cap, nnz_out,
+                                                          workspace, (hipStream_t)stream);
+    return e == hipSuccess ? AP_OK : AP_ERR_HIP;
+}
+
 ap_status ap_build_schedule(const int32_t* row_ptr, const int32_t* col_idx, const uint64_t* bitmaps,
                             int H, int Lq, int Lk, int block_m, int block_n, int64_t cap, int causal,
                             int min_cols, const ap_schedule* sched, void* stream)
@@ -560,7 +582,7 @@ ap_status ap_prune_mask(const float* abar, int H, int Lq, int Lk, int causal, do
                         uint8_t* mask, float* tau_out, void* workspace, size_t workspace_bytes,
                         void* stream)
 {
-    if (!abar || !mask || !workspace) return AP_ERR_INVALID_ARG;
+    if (!abar || (!mask && !tau_out) || !workspace) return AP_ERR_INVALID_ARG;
     if (H <= 0 || Lq <= 0 || Lk <= 0) return AP_ERR_INVALID_ARG;
     if (!(prune_fraction >= 0.0 && prune_fraction <= 1.0)) return AP_ERR_INVALID_ARG;   // also NaN
     if (causal && Lk < Lq) return AP_ERR_INVALID_ARG;

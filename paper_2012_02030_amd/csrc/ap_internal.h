@@ -16,6 +16,12 @@ hipError_t launch_build_layout(const uint8_t* mask, long long stride_h, long lon
                                uint64_t* bitmaps, long long cap, int64_t* nnz_out, void* workspace,
                                hipStream_t stream);
 
+// the same from the fp32 mean map and the layer's threshold (device scalar): kept iff not
+// (abar < tau) and, if causal, j <= i + (Lk - Lq); 64-key windows only
+hipError_t launch_build_layout_from_map(const float* abar, const float* tau, int causal, int H, int Lq, int Lk,
+                                        int BM, int BN, int32_t* row_ptr, int32_t* col_idx, uint64_t* bitmaps,
+                                        long long cap, int64_t* nnz_out, void* workspace, hipStream_t stream);
+
 // ---- visit schedule (ap_schedule.hip): entry e of block row r is element row_ptr[r] + e
 struct Schedule {
     int32_t* cnt;        // [H*nQB]      entries of each block row

@@ -365,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void mask_collect_kernel(Walk w, Workspac
                 }
                 // candidates get 0 here, their byte comes later; a quad cut by the visible prefix
                 // also writes the zeros of its hidden entries (inside the row)
-                if (q[k].cnt > 0) {
+                if (mask && q[k].cnt > 0) {
                     uint8_t* dst = mask + lin;
                     if (vec_ok) {
                         *reinterpret_cast<uint32_t*>(dst) = out;
@@ -379,7 +379,7 @@ __global__ __launch_bounds__(kThreads) void mask_collect_kernel(Walk w, Workspac
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const bool present = r == 0 || u.base[1] != u.base[0];
-            if (!present) continue;
+            if (!present || !mask) continue;
             int start = none ? 0 : u.n[r];
             if (vec_ok) start = none ? 0 : (start + 3) & ~3;
             uint8_t* dst = mask + u.base[r];
@@ -494,7 +494,7 @@ hipError_t launch_prune_mask(const float* abar, int H, int Lq, int Lk, int causa
     hipLaunchKernelGGL(mask_collect_kernel, dim3(grid2), dim3(kThreads), 0, stream, w, ws, mask, none_i);
     if (!none) {
         hipLaunchKernelGGL(candidate_select_kernel, dim3(1), dim3(kThreads), 0, stream, ws, tau_out);
-        hipLaunchKernelGGL(candidate_fixup_kernel, dim3(256), dim3(256), 0, stream, ws, mask);
+        if (mask) hipLaunchKernelGGL(candidate_fixup_kernel, dim3(256), dim3(256), 0, stream, ws, mask);
     }
     return hipGetLastError();
 }

@@ -167,7 +167,7 @@ def test_mask_construction_arguments(L):
                                a["tau"], a["ws"], a["ws_bytes"], None)
 
     assert prune(abar=None) == ap.AP_ERR_INVALID_ARG
-    assert prune(mask=None) == ap.AP_ERR_INVALID_ARG
+    assert prune(mask=None, tau=None) == ap.AP_ERR_INVALID_ARG    # nothing to write (mask = NULL alone: threshold only)
     assert prune(Lk=0) == ap.AP_ERR_INVALID_ARG
     assert prune(p=-0.1) == ap.AP_ERR_INVALID_ARG
     assert prune(p=1.5) == ap.AP_ERR_INVALID_ARG
@@ -432,6 +432,30 @@ def test_binding_rejects_caller_supplied_outputs_that_do_not_fit():
     for lse in bad_lses:
         with pytest.raises(ValueError):
             ap.ap_sparse_attn_fwd(q, k, k, lay, lse=lse)
+
+
+def test_layout_from_map_arguments(L):
+    fake = 0x1000
+    ws = ap.ap_layout_workspace_bytes(2, 128, 128, 64, 64)
+
+    def call(**over):
+        a = dict(abar=fake, tau=fake + 0x100, H=2, Lq=128, Lk=128, causal=0, bm=64, bn=64, rp=fake, ci=fake,
+                 bmp=fake, cap=8, ws=fake, ws_bytes=ws)
+        a.update(over)
+        return L.ap_build_layout_from_map(a["abar"], a["tau"], a["H"], a["Lq"], a["Lk"], a["causal"], a["bm"],
+                                          a["bn"], a["rp"], a["ci"], a["bmp"], a["cap"], None, a["ws"],
+                                          a["ws_bytes"], None)
+
+    assert call(abar=None) == ap.AP_ERR_INVALID_ARG
+    assert call(tau=None) == ap.AP_ERR_INVALID_ARG
+    assert call(H=0) == ap.AP_ERR_INVALID_ARG
+    assert call(bn=32) == ap.AP_ERR_UNSUPPORTED
+    assert call(bm=48) == ap.AP_ERR_UNSUPPORTED
+    assert call(causal=1, Lq=128, Lk=64) == ap.AP_ERR_INVALID_ARG
+    assert call(ci=None) == ap.AP_ERR_INVALID_ARG            # col_idx and bitmaps go together
+    assert call(cap=-1) == ap.AP_ERR_INVALID_ARG
+    assert call(ws_bytes=ws - 1) == ap.AP_ERR_CAPACITY
+    assert call(tau=fake + 2) == ap.AP_ERR_INVALID_ARG
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -5,7 +5,8 @@ bf16 inputs; the kernel forms the scores in fp32 on the matrix cores (relative e
 about 2^-23 * sqrt(D), absolute about 5e-5 for |s| ~ 40), takes exp2 and log2 with the
 hardware approximations (about 2^-22 relative) and sums B probabilities <= 1 in fp32, so a
 probability is off by at most about 1e-4 of itself.
-Threshold and mask: bit-exact on the same float32 input.
+Threshold and mask: bit-exact on the same float32 input; so is the layout built straight from the
+map and the threshold (ap_build_layout_from_map) against the layout oracle on the oracle's mask.
 """
 import numpy as np
 import pytest
@@ -15,7 +16,7 @@ import oracle
 from paper_2012_02030_amd import binding as ap
 from paper_2012_02030_amd import synth
 
-from gpu_util import to_device
+from gpu_util import assert_layout_equal, to_device
 
 pytestmark = pytest.mark.gpu
 MAP_TOL = 1e-4
@@ -120,7 +121,7 @@ def abar_from_oracle(H, Lq, Lk, causal, seed):
     return oracle.mean_attention_map(Q, K, causal=causal).astype(np.float32)
 
 
-def check_prune(abar_np, p, causal):
+def check_prune(abar_np, p, causal, layout_block_ms=(64, 128)):
     d = torch.from_numpy(abar_np).cuda()
     mask, tau = ap.ap_prune_mask(d, p, causal=causal)
     torch.cuda.synchronize()
@@ -128,6 +129,15 @@ def check_prune(abar_np, p, causal):
     got_tau = tau.cpu().numpy()[0]
     assert got_tau == ref_tau or (np.isinf(got_tau) and np.isinf(ref_tau)), (got_tau, ref_tau)
     assert np.array_equal(mask.cpu().numpy(), ref_mask)
+    # the same without the byte mask: threshold only, then the layout straight from the map; it must
+    # be the layout of the oracle's mask (Eq. (2)'s strict comparison, ties kept, hidden entries never)
+    none, tau2 = ap.ap_prune_mask(d, p, causal=causal, threshold_only=True)
+    assert none is None
+    for bm in layout_block_ms:
+        lay = ap.ap_build_layout_from_map(d, tau2, causal=causal, block_m=bm)
+        torch.cuda.synchronize()
+        assert torch.equal(tau2, tau)
+        assert_layout_equal(lay, ref_mask)
 
 
 @pytest.mark.parametrize("p", [0.0, 0.1, 0.5, 0.9, 0.999, 1.0])
@@ -219,4 +229,4 @@ def test_full_size_threshold_and_mask_bit_exact():
     """H16 x 4096 x 4096 causal map (the benchmark's shape), prune 90 %: tau and every mask byte
     equal the oracle's on the same float32 input."""
     a = synth.make_mean_map(16, 4096, 4096, seed=5)
-    check_prune(a, 0.9, True)
+    check_prune(a, 0.9, True, layout_block_ms=(64,))
