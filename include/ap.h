@@ -205,6 +205,28 @@ ap_status ap_sparse_attn_fwd(const void *Q, const void *K, const void *V, void *
                              const ap_schedule *sched, int causal, float softmax_scale,
                              void *stream);
 
+/*
+ * The same under the top-left Lq x Lk corner of a mask whose layout (and schedule) were built once
+ * for Lq_layout x Lk_layout (Section 6: sequence lengths vary across a data set while the mask of
+ * a layer and head is fixed): one layout serves every length, nothing is rebuilt per call.  The
+ * result is that of ap_sparse_attn_fwd with the layout of the cropped mask (ap_build_layout_cropped).
+ *
+ *   Lq <= Lq_layout, Lk <= Lk_layout; Q, O have Lq rows, K, V have Lk rows
+ *   causal        as in ap_sparse_attn_fwd, aligned to THIS call's sizes: j <= i + (Lk - Lq).  A
+ *                 schedule has the limit of the layout's sizes folded in, so with `causal` and a
+ *                 schedule Lk - Lq must equal Lk_layout - Lq_layout (e.g. self-attention cropped
+ *                 to a shorter length), else AP_ERR_INVALID_ARG
+ *   everything else as in ap_sparse_attn_fwd.  Supported: dtype = AP_BF16.
+ */
+ap_status ap_sparse_attn_fwd_cropped(const void *Q, const void *K, const void *V, void *O, float *lse,
+                                     ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                     const int64_t *stride_q, const int64_t *stride_k,
+                                     const int64_t *stride_v, const int64_t *stride_o,
+                                     const int32_t *row_ptr, const int32_t *col_idx,
+                                     const uint64_t *bitmaps, int block_m, int block_n, int Lq_layout,
+                                     int Lk_layout, const ap_schedule *sched, int causal,
+                                     float softmax_scale, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Masked attention forward for few queries against many keys (the Transformer-XL setting of
  * Section 4.1: a short segment attends to a long cached memory; the mask of such a layer is

@@ -25,7 +25,7 @@ AP_F32 = 0
 AP_BF16 = 1
 
 SYMBOLS = ("ap_status_string", "ap_layout_max_tiles", "ap_layout_workspace_bytes",
-           "ap_build_layout", "ap_build_layout_cropped", "ap_build_layout_from_map", "ap_build_schedule", "ap_sparse_attn_fwd",
+           "ap_build_layout", "ap_build_layout_cropped", "ap_build_layout_from_map", "ap_build_schedule", "ap_sparse_attn_fwd", "ap_sparse_attn_fwd_cropped",
            "ap_sparse_attn_entmax15_fwd", "ap_fwd_split_workspace_bytes", "ap_sparse_attn_fwd_split",
            "ap_sparse_attn_fwd_split_static", "ap_sparse_attn_decode",
            "ap_build_layout_transpose", "ap_bwd_workspace_bytes", "ap_sparse_attn_bwd",
@@ -85,6 +85,12 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(i64), ctypes.POINTER(i64),
                                          vp, vp, vp, i32, i32, ctypes.POINTER(_CSchedule), i32,
                                          ctypes.c_float, vp]
+        L.ap_sparse_attn_fwd_cropped.restype = i32
+        L.ap_sparse_attn_fwd_cropped.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
+                                                 ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                                 ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                                 vp, vp, vp, i32, i32, i32, i32, ctypes.POINTER(_CSchedule), i32,
+                                                 ctypes.c_float, vp]
         L.ap_sparse_attn_decode.restype = i32
         L.ap_sparse_attn_decode.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32,
                                             ctypes.POINTER(i64), ctypes.POINTER(i64),
@@ -326,9 +332,11 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
                        causal: bool = False, softmax_scale: float = 0.0,
                        out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
                        return_lse: bool = True, stream: Optional[torch.cuda.Stream] = None,
-                       sched: Optional[Schedule] = None):
+                       sched: Optional[Schedule] = None, crop: bool = False):
     """Q [B,H,Lq,D], K/V [B,H,Lk,D] device tensors (fp32 or bf16, last dim contiguous).
 
+    crop=True: Lq, Lk may be smaller than the sizes the layout was built for; the call then runs
+    under the top-left corner of that mask (ap_sparse_attn_fwd_cropped).
     Returns (O, lse); lse is None when return_lse is False.  Asynchronous on the stream.
     """
     if Q.dtype == torch.bfloat16:
@@ -345,7 +353,8 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
     Lk = K.shape[2]
     if tuple(K.shape) != (B, H, Lk, D) or tuple(V.shape) != (B, H, Lk, D):
         raise ValueError("K/V shape mismatch")
-    if (H, Lq, Lk) != (layout.H, layout.Lq, layout.Lk):
+    cropped = (Lq, Lk) != (layout.Lq, layout.Lk)
+    if H != layout.H or Lq > layout.Lq or Lk > layout.Lk or (cropped and not crop):
         raise ValueError("layout was built for other sizes")
     for t in (Q, K, V):
         if t.stride(3) != 1:
@@ -361,13 +370,17 @@ def ap_sparse_attn_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, layout
         lse = torch.empty((B, H, Lq), dtype=torch.float32, device=Q.device)
     elif lse is not None:
         _check_rows_f32(lse, Q, "lse")
-    st = lib().ap_sparse_attn_fwd(
-        Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
-        lse.data_ptr() if lse is not None else None, dt, B, H, Lq, Lk, D,
-        _strides3(Q), _strides3(K), _strides3(V), _strides3(out),
-        layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
-        layout.block_m, layout.block_n, ctypes.byref(cs) if cs is not None else None,
-        int(bool(causal)), float(softmax_scale), _stream_ptr(stream))
+    head = (Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+            lse.data_ptr() if lse is not None else None, dt, B, H, Lq, Lk, D,
+            _strides3(Q), _strides3(K), _strides3(V), _strides3(out),
+            layout.row_ptr.data_ptr(), layout.col_idx.data_ptr(), layout.bitmaps.data_ptr(),
+            layout.block_m, layout.block_n)
+    tail = (ctypes.byref(cs) if cs is not None else None, int(bool(causal)), float(softmax_scale),
+            _stream_ptr(stream))
+    if crop:
+        st = lib().ap_sparse_attn_fwd_cropped(*head, layout.Lq, layout.Lk, *tail)
+    else:
+        st = lib().ap_sparse_attn_fwd(*head, *tail)
     if st != AP_OK:
         raise ApError(st, "ap_sparse_attn_fwd")
     return out, lse

@@ -170,8 +170,18 @@ static ap_status fwd_common(const void* Q, const void* K, const void* V, void* O
                             const uint64_t* bitmaps, int block_m, int block_n,
                             const ap_schedule* sched, int causal, float softmax_scale, int splits,
                             void* workspace, size_t workspace_bytes, void* stream, bool entmax = false,
-                            bool decode = false)
+                            bool decode = false, int Lq_layout = 0, int Lk_layout = 0)
 {
+    // cropped call: the layout (and schedule) were built for Lq_layout x Lk_layout, this call uses
+    // the top-left Lq x Lk corner of that mask
+    const bool cropped = Lq_layout > 0 || Lk_layout > 0;
+    if (cropped) {
+        if (Lq_layout < Lq || Lk_layout < Lk) return AP_ERR_INVALID_ARG;
+        if (causal && Lk_layout < Lq_layout) return AP_ERR_INVALID_ARG;
+        // a schedule has the causal limit of its own sizes folded into its bitmaps
+        if (causal && sched && (long long)Lk - Lq != (long long)Lk_layout - Lq_layout) return AP_ERR_INVALID_ARG;
+        if (dtype != AP_BF16) return AP_ERR_UNSUPPORTED;
+    }
     if (!Q || !K || !V || !O || !stride_q || !stride_k || !stride_v || !stride_o || !row_ptr ||
         !col_idx || !bitmaps)
         return AP_ERR_INVALID_ARG;
@@ -235,6 +245,8 @@ static ap_status fwd_common(const void* Q, const void* K, const void* V, void* O
         a.sched = ap::Schedule{sched->cnt, sched->start, sched->cols, sched->bitmaps};
     else
         a.sched = ap::Schedule{nullptr, nullptr, nullptr, nullptr};
+    a.nqb_layout = (int)(((long long)(cropped ? Lq_layout : Lq) + block_m - 1) / block_m);
+    a.crop = (cropped && Lk < Lk_layout) ? 1 : 0;
     a.splits = splits > 0 ? splits : 1;
     a.part_o = (float*)workspace;
     a.part_lse = a.part_o ? a.part_o + (size_t)a.splits * B * H * Lq * D : nullptr;
@@ -264,6 +276,21 @@ ap_status ap_sparse_attn_fwd(const void* Q, const void* K, const void* V, void* 
     return fwd_common(Q, K, V, O, lse, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v, stride_o,
                       row_ptr, col_idx, bitmaps, block_m, block_n, sched, causal, softmax_scale, 0,
                       nullptr, 0, stream);
+}
+
+ap_status ap_sparse_attn_fwd_cropped(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                     ap_dtype dtype, int B, int H, int Lq, int Lk, int D,
+                                     const int64_t* stride_q, const int64_t* stride_k,
+                                     const int64_t* stride_v, const int64_t* stride_o,
+                                     const int32_t* row_ptr, const int32_t* col_idx,
+                                     const uint64_t* bitmaps, int block_m, int block_n, int Lq_layout,
+                                     int Lk_layout, const ap_schedule* sched, int causal,
+                                     float softmax_scale, void* stream)
+{
+    if (Lq_layout <= 0 || Lk_layout <= 0) return AP_ERR_INVALID_ARG;
+    return fwd_common(Q, K, V, O, lse, dtype, B, H, Lq, Lk, D, stride_q, stride_k, stride_v, stride_o,
+                      row_ptr, col_idx, bitmaps, block_m, block_n, sched, causal, softmax_scale, 0,
+                      nullptr, 0, stream, false, false, Lq_layout, Lk_layout);
 }
 
 ap_status ap_sparse_attn_decode(const void* Q, const void* K, const void* V, void* O, float* lse,

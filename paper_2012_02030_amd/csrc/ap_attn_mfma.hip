@@ -120,7 +120,7 @@ __global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd
     float lsum = 0.f;                                        // this lane's share of the row sum
     const float sc = a.scale * kLog2e;
 
-    const int r = h * nQB + qb;
+    const int r = h * a.nqb_layout + qb;
     int t_begin = a.row_ptr[r];
     int nt = SCHED ? a.sched.cnt[r] : a.row_ptr[r + 1] - t_begin;
     if (SPLIT) {                                             // this workgroup's chunk of the entries
@@ -358,6 +358,18 @@ __global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd
         }
         return word;
     };
+    // A layout built for more keys than this call has (a fixed mask, a shorter sequence): the slots
+    // of an entry whose key exists.  slot = the metadata slot that holds the entry's gather keys;
+    // must be called before that slot is handed to a later entry.
+    auto crop_valid = [&](int k0, int slot) -> uint64_t {
+        if (!a.crop) return ~0ull;                           // uniform
+        if (!SCHED || k0 >= 0) {
+            const long long lim = (long long)a.Lk - 1 - k0;
+            return lim < 0 ? 0ull : (lim < 63 ? (2ull << lim) - 1ull : ~0ull);
+        }
+        const int key = *reinterpret_cast<const int*>(smem + TILES + 2 * META_W + slot * META_C + lane * 2);
+        return __ballot(key < a.Lk);
+    };
 
     int gidx[NLOAD];                                         // gather keys of the next tile to be issued
 #pragma unroll
@@ -395,7 +407,7 @@ __global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd
 
             wait_vmem();                                     // my loads of this tile have landed
             __syncthreads();                                 // ... and everybody else's
-            uint64_t word = read_word(stage);
+            uint64_t word = read_word(stage) & crop_valid(k0, stage);
             if (it + 1 < nt) {
                 k0_next = tile_start(it + 1);
                 if (SCHED && k0_next < 0) read_cols(stage ^ 1, gidx);
@@ -444,6 +456,7 @@ __global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd
             const int slot = it & 1;
             wait_vmem();                                     // K and metadata of this tile (keys of the next)
             __syncthreads();                                 // ... for everybody; the V buffer is free
+            const uint64_t valid = crop_valid(s_cur, slot);
             // metadata of later tiles first, so that only the K loads are younger than the V loads
             int s_nn = 0;
             if (it + 1 < nt) dma_words(it + 1, slot ^ 1);
@@ -453,7 +466,7 @@ __global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd
             }
             if (!SCHED || s_cur >= 0) issue_tile_loads<D, NW, true>(v_rsrc, Vs, s_cur, sv_bytes, wave, lane);
             else issue_gather_loads<D, NW, true>(v_rsrc, Vs, gcur, sv_bytes, wave, lane);
-            const uint64_t word = apply_causal(read_word(slot), s_cur);
+            const uint64_t word = apply_causal(read_word(slot), s_cur) & valid;
             const bool active = __ballot(word != 0) != 0;    // something visible for these 32 queries
             f32x16 sacc[2];
             if (active) qk_tile(Ks, sacc);

@@ -50,6 +50,8 @@ struct FwdArgs {
     int causal;
     float scale;                    // already resolved (> 0)
     Schedule sched;                 // all null: walk the layout itself
+    int nqb_layout;                 // block rows per head of the layout (> those of Lq for a cropped call)
+    int crop;                       // 1: the layout covers more keys than Lk; keys >= Lk are hidden
     int splits;                     // split path only: chunks per block row
     float* part_o;                  // [splits, B, H, Lq, D] fp32 partial outputs
     float* part_lse;                // [splits, B, H, Lq]

@@ -99,6 +99,27 @@ def test_fwd_rejects_bad_arguments(L):
     assert _fwd(L, scale=float("nan")) == ap.AP_ERR_INVALID_ARG
 
 
+def test_cropped_forward_arguments(L):
+    fake = 0x1000
+    s = (ctypes.c_int64 * 3)(2 * 64 * 64, 64 * 64, 64)
+
+    def call(**over):
+        a = dict(Lq=64, Lk=64, Lql=128, Lkl=128, dtype=ap.AP_BF16, causal=0, sched=None)
+        a.update(over)
+        return L.ap_sparse_attn_fwd_cropped(fake, fake + 0x100000, fake + 0x200000, fake + 0x300000, None,
+                                            a["dtype"], 1, 2, a["Lq"], a["Lk"], 64, s, s, s, s, fake, fake, fake,
+                                            64, 64, a["Lql"], a["Lkl"], a["sched"], a["causal"], 0.0, None)
+
+    assert call(Lql=0) == ap.AP_ERR_INVALID_ARG
+    assert call(Lql=32) == ap.AP_ERR_INVALID_ARG              # layout smaller than the call
+    assert call(Lkl=63) == ap.AP_ERR_INVALID_ARG
+    assert call(dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    cs = ap._CSchedule(fake, fake, fake, fake)
+    # causal with a schedule: the offsets Lk - Lq of call and layout must agree
+    assert call(causal=1, Lq=32, Lk=64, sched=ctypes.byref(cs)) == ap.AP_ERR_INVALID_ARG
+    assert call(causal=1, Lql=128, Lkl=64) == ap.AP_ERR_INVALID_ARG
+
+
 def test_schedule_arguments(L):
     fake = 0x1000
     good = ap._CSchedule(fake, fake, fake, fake)
