@@ -220,6 +220,28 @@ def main():
         res["tolerance"] = 2e-2 if cfg.dtype == "bf16" else 1e-5
         return res, all_s
 
+    def schedule_classes(layout, sched, block_m):
+        """Entries of the two kinds of the visit schedule (per layer), the share of their 64 x block_m
+        slots that hold a kept pair, and in how many entries a 32-query group (one wavefront of the
+        attention kernel) has nothing to do."""
+        rp = layout.row_ptr.cpu().numpy().astype(np.int64)
+        cnt = sched.cnt.cpu().numpy().astype(np.int64)
+        idx = np.concatenate([np.arange(rp[r], rp[r] + cnt[r]) for r in range(len(cnt))]) if cnt.sum() else \
+            np.zeros(0, np.int64)
+        start = sched.start.cpu().numpy()[idx]
+        words = sched.bitmaps.cpu().numpy().view(np.uint64)[idx]                  # [entries, block_m]
+        pop = np.unpackbits(words.view(np.uint8), axis=-1).reshape(len(idx), -1).sum(axis=1)
+        groups = (words.reshape(len(idx), block_m // 32, 32) != 0).any(axis=2)       # [entries, 32-query groups]
+        out = {}
+        for name, sel in (("consecutive", start >= 0), ("gathered", start < 0)):
+            n = int(sel.sum())
+            out[name] = {"entries": n,
+                         "kept_pairs": int(pop[sel].sum()),
+                         "slot_fill": float(pop[sel].sum()) / (n * 64.0 * block_m) if n else None,
+                         "entries_x_groups_with_work": int(groups[sel].sum()),
+                         "entries_x_groups": n * (block_m // 32)}
+        return out
+
     def run_config(cfg, mask_np, steps, warmup, block_m, use_graph):
         """AP-mask run and dense-mask run of the same kernel; returns a result dict."""
         dmask = torch.from_numpy(mask_np).to(dev)
@@ -247,8 +269,8 @@ def main():
 
         sets, outs, lses = tensor_sets(cfg, n_sets_for(cfg))
         wall_ms, per = time_calls(cfg, layout, sets, outs, lses, steps, warmup, sched)
-        dsteps = max(10, steps // 4)
-        dwall_ms, dper = time_calls(cfg, dense_layout, sets, outs, lses, dsteps, max(2, warmup // 4))
+        dsteps = steps                                               # same steps and warm-up as the AP-mask leg
+        dwall_ms, dper = time_calls(cfg, dense_layout, sets, outs, lses, dsteps, warmup)
         ms = float(np.mean(per))
         dms = float(np.mean(dper))
         # warm: one buffer set only, so K, V and Q may stay in the 256 MB cache between calls
@@ -273,6 +295,7 @@ def main():
         dense_flop = 4.0 * cfg.D * dense_entries * cfg.B
         nnz = int(layout.nnz.item())
         visited = int(sched.cnt.sum().item()) if sched is not None else nnz
+        classes = schedule_classes(layout, sched, block_m) if sched is not None else None
         tile_flop = 4.0 * cfg.D * block_m * 64 * visited * cfg.B           # matrix-core work of the visited tiles
         res = {
             "shape": {"B": cfg.B, "H": cfg.H, "Lq": cfg.Lq, "Lk": cfg.Lk, "D": cfg.D,
@@ -282,6 +305,7 @@ def main():
             "tiles_stored": nnz,
             "tiles_visited": visited,
             "schedule_ms": sched_ms,
+            "schedule_entries": classes,
             "tiles_max": int(ap.ap_layout_max_tiles(cfg.H, cfg.Lq, cfg.Lk, block_m, 64)),
             "ms_per_call": kernel_ms,
             "ms_per_call_stream_launches": ms,
@@ -346,6 +370,10 @@ def main():
 
         prune_ms = timed(prune, steps)
         lay_ms = timed(lambda: ap.ap_build_layout(keep["mask"], args.block_m, 64), steps)
+        # without the byte mask: threshold only, then the layout straight from the map (Eq. (2) in the scan)
+        tau_ms = timed(lambda: ap.ap_prune_mask(abar, p, causal=cfg.causal, threshold_only=True), steps)
+        map_lay_ms = timed(lambda: ap.ap_build_layout_from_map(abar, keep["tau"], causal=cfg.causal,
+                                                               block_m=args.block_m), steps)
         if cfg.causal:
             vis = cfg.H * sum(min(cfg.Lk, i + 1 + cfg.Lk - cfg.Lq) for i in range(cfg.Lq))
         else:
@@ -371,6 +399,9 @@ def main():
             "prune_mask_gbs": prune_bytes / (prune_ms * 1e-3) / 1e9,
             "prune_mask_hbm_frac": prune_bytes / (prune_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "layout_ms": lay_ms,
+            "threshold_only_ms": tau_ms,
+            "layout_from_map_ms": map_lay_ms,
+            "map_to_layout_ms": {"via_byte_mask": prune_ms + lay_ms, "without_byte_mask": tau_ms + map_lay_ms},
             "tau": float(keep["tau"].item()),
             "kept_entries": kept,
             "kept_fraction_of_visible": kept / float(vis),
@@ -537,6 +568,47 @@ def main():
             "hbm_roofline_frac": alg / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         }
 
+    def run_cropped(cfg, mask_np, steps):
+        """Half-length sequences under the full-length mask: the cropped call on the layout and
+        schedule built once for the full size, against the ordinary call on a layout and schedule
+        rebuilt for the corner (and what that rebuild costs)."""
+        if cfg.dtype != "bf16" or cfg.Lq != cfg.Lk:
+            return None
+        L = cfg.Lq // 2
+        dmask = torch.from_numpy(mask_np).to(dev)
+        lay = ap.ap_build_layout(dmask, 64, 64)
+        sched = ap.ap_build_schedule(lay, causal=cfg.causal, min_cols=args.min_cols)
+        q, k, v = (torch.from_numpy(np.ascontiguousarray(x[:, :, :L])).to(torch.bfloat16).to(dev)
+                   for x in synth.make_qkv(cfg))
+        out = torch.empty_like(q)
+
+        def timed(fn, n):
+            fn()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+            torch.cuda.synchronize()
+            evs[0].record()
+            for i in range(n):
+                fn()
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            return float(np.mean([evs[i].elapsed_time(evs[i + 1]) for i in range(n)]))
+
+        crop_ms = timed(lambda: ap.ap_sparse_attn_fwd(q, k, v, lay, causal=cfg.causal, out=out, sched=sched,
+                                                      crop=True), steps)
+        rebuilt = {}
+
+        def rebuild():
+            rebuilt["lay"] = ap.ap_build_layout(dmask, 64, 64, crop=(L, L))
+            rebuilt["sched"] = ap.ap_build_schedule(rebuilt["lay"], causal=cfg.causal, min_cols=args.min_cols)
+
+        rebuild_ms = timed(rebuild, steps)
+        plain_ms = timed(lambda: ap.ap_sparse_attn_fwd(q, k, v, rebuilt["lay"], causal=cfg.causal, out=out,
+                                                       sched=rebuilt["sched"]), steps)
+        return {"shape": {"B": cfg.B, "H": cfg.H, "Lq": L, "Lk": L, "D": cfg.D, "causal": cfg.causal,
+                          "layout_built_for": [cfg.Lq, cfg.Lk]},
+                "cropped_call_ms": crop_ms, "call_on_rebuilt_layout_ms": plain_ms,
+                "rebuild_layout_and_schedule_ms": rebuild_ms}
+
     def run_entmax(cfg, mask_np, steps):
         """1.5-entmax forward of cfg under its AP mask (plain layout walk) next to the softmax
         forward over the same layout walk."""
@@ -687,6 +759,12 @@ def main():
         decode = run_decode(synth.EXTRA_CONFIGS["X1"], 20)
         torch.cuda.empty_cache()
 
+    cropped = None
+    if not args.only:
+        log("timing the cropped forward call at half of the", head.name, "length ...")
+        cropped = run_cropped(head, head_mask, 20)
+        torch.cuda.empty_cache()
+
     entmax = None
     if not args.only:
         log("timing the 1.5-entmax forward at the", head.name, "shape ...")
@@ -737,6 +815,7 @@ def main():
         "mask_construction": mask_construction,
         "backward": backward,
         "split_forward": split_forward,
+        "cropped_forward": cropped,
         "decode": decode,
         "entmax15_forward": entmax,
         "per_config": per_config,
