@@ -193,8 +193,9 @@ ap_status ap_build_schedule(const int32_t *row_ptr, const int32_t *col_idx, cons
  *   causal        nonzero = also hide future keys; requires Lk >= Lq
  *   softmax_scale <= 0 selects 1/sqrt(D)
  *
- * Supported: D in {32, 64, 128}; block_n = 64; block_m = 64 (both dtypes) or 128 (bf16).
- * Returns AP_ERR_UNSUPPORTED otherwise.
+ * Supported: D in {32, 64, 128}; block_n = 64; block_m = 64 (both dtypes) or 128 (bf16); with a
+ * schedule (here and in every call below that takes one), sequence lengths and row strides in
+ * bytes below 2^24.  Returns AP_ERR_UNSUPPORTED otherwise.
  * ------------------------------------------------------------------------------------------- */
 ap_status ap_sparse_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *lse,
                              ap_dtype dtype, int B, int H, int Lq, int Lk, int D,

@@ -218,6 +218,10 @@ static ap_status fwd_common(const void* Q, const void* K, const void* V, void* O
                              (long long)Lk * stride_v[2] * 2 >= 2147483647LL))
         return AP_ERR_UNSUPPORTED;
 
+    // gathered rows are addressed as key * row stride with the 24-bit multiply
+    if (sched && (Lk >= (1LL << 24) || stride_k[2] * 2 >= (1LL << 24) || stride_v[2] * 2 >= (1LL << 24)))
+        return AP_ERR_UNSUPPORTED;
+
     if (entmax && (dtype != AP_BF16 || block_m != 64)) return AP_ERR_UNSUPPORTED;
     // one workgroup per query there
     if (decode && (dtype != AP_BF16 || sched || (long long)B * H * Lq >= 2147483647LL)) return AP_ERR_UNSUPPORTED;
@@ -432,6 +436,12 @@ static ap_status bwd_common(const void* Q, const void* K, const void* V, const v
     // bitmap rows are fetched with 32-bit byte offsets: 512 bytes per tile
     if (nQB * nKB * H >= (1LL << 22)) return AP_ERR_UNSUPPORTED;
     if (workspace_bytes < ap_bwd_workspace_bytes(B, H, Lq)) return AP_ERR_CAPACITY;
+    // gathered rows (keys for one schedule, queries for the other) are addressed as row index * row
+    // stride with the 24-bit multiply
+    if ((sched || col_sched) &&
+        (Lk >= (1LL << 24) || Lq >= (1LL << 24) || stride_k[2] * 2 >= (1LL << 24) || stride_v[2] * 2 >= (1LL << 24) ||
+         stride_q[2] * 2 >= (1LL << 24) || stride_o[2] * 2 >= (1LL << 24)))
+        return AP_ERR_UNSUPPORTED;
     for (const ap_schedule* sc : {sched, col_sched}) {
         if (!sc) continue;
         if (!sc->cnt || !sc->start || !sc->cols || !sc->bitmaps) return AP_ERR_INVALID_ARG;

@@ -87,9 +87,66 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned num_bytes
 
 __device__ __forceinline__ unsigned lds_addr_of(lds_u16* p) { return (unsigned)(uintptr_t)p; }
 
+// N such loads in a row, as one instruction sequence: load u puts 1 KB at lds_addr + u * LSTEP
+// and reads at per-lane offset voff[u] plus scalar offset soff + u * sstep.  M0 and the scalar
+// offset advance by one scalar addition each between two loads (the second one also provides the
+// wait state that a write of M0 needs before the next LDS-direct load), so a load costs three
+// instructions and no vector arithmetic.
+#define AP_DMA_LD(v) "buffer_load_dwordx4 %[" v "], %[rs], %[t] offen lds\n\t"
+#define AP_DMA_NX "s_add_u32 m0, m0, %[ls]\n\ts_add_u32 %[t], %[t], %[ss]\n\t"
+#define AP_DMA_HEAD "s_mov_b32 m0, %[lds]\n\ts_mov_b32 %[t], %[so]\n\t"
+template <int N, int LSTEP>
+__device__ __forceinline__ void load16_chain(unsigned lds_addr, int soff, int sstep, const int* voff, rsrc_t rsrc)
+{
+    static_assert(N == 1 || N == 2 || N == 4 || N == 8, "loads per wavefront, operand and tile");
+    rsrc.x = __builtin_amdgcn_readfirstlane(rsrc.x);         // wave-uniform by construction, see above
+    rsrc.y = __builtin_amdgcn_readfirstlane(rsrc.y);
+    rsrc.z = __builtin_amdgcn_readfirstlane(rsrc.z);
+    rsrc.w = __builtin_amdgcn_readfirstlane(rsrc.w);
+    soff = __builtin_amdgcn_readfirstlane(soff);
+    sstep = __builtin_amdgcn_readfirstlane(sstep);
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+    int t;
+    if constexpr (N == 1)
+        asm volatile(AP_DMA_HEAD AP_DMA_LD("v0")
+                     : [t] "=&s"(t)
+                     : [lds] "s"(lds_addr), [so] "s"(soff), [rs] "s"(rsrc), [v0] "v"(voff[0])
+                     : "memory", "m0");
+    else if constexpr (N == 2)
+        asm volatile(AP_DMA_HEAD AP_DMA_LD("v0") AP_DMA_NX AP_DMA_LD("v1")
+                     : [t] "=&s"(t)
+                     : [lds] "s"(lds_addr), [so] "s"(soff), [ss] "s"(sstep), [ls] "n"(LSTEP), [rs] "s"(rsrc),
+                       [v0] "v"(voff[0]), [v1] "v"(voff[1])
+                     : "memory", "m0", "scc");
+    else if constexpr (N == 4)
+        asm volatile(AP_DMA_HEAD AP_DMA_LD("v0") AP_DMA_NX AP_DMA_LD("v1") AP_DMA_NX AP_DMA_LD("v2")
+                         AP_DMA_NX AP_DMA_LD("v3")
+                     : [t] "=&s"(t)
+                     : [lds] "s"(lds_addr), [so] "s"(soff), [ss] "s"(sstep), [ls] "n"(LSTEP), [rs] "s"(rsrc),
+                       [v0] "v"(voff[0]), [v1] "v"(voff[1]), [v2] "v"(voff[2]), [v3] "v"(voff[3])
+                     : "memory", "m0", "scc");
+    else
+        asm volatile(AP_DMA_HEAD AP_DMA_LD("v0") AP_DMA_NX AP_DMA_LD("v1") AP_DMA_NX AP_DMA_LD("v2")
+                         AP_DMA_NX AP_DMA_LD("v3") AP_DMA_NX AP_DMA_LD("v4") AP_DMA_NX AP_DMA_LD("v5")
+                             AP_DMA_NX AP_DMA_LD("v6") AP_DMA_NX AP_DMA_LD("v7")
+                     : [t] "=&s"(t)
+                     : [lds] "s"(lds_addr), [so] "s"(soff), [ss] "s"(sstep), [ls] "n"(LSTEP), [rs] "s"(rsrc),
+                       [v0] "v"(voff[0]), [v1] "v"(voff[1]), [v2] "v"(voff[2]), [v3] "v"(voff[3]),
+                       [v4] "v"(voff[4]), [v5] "v"(voff[5]), [v6] "v"(voff[6]), [v7] "v"(voff[7])
+                     : "memory", "m0", "scc");
+}
+#undef AP_DMA_LD
+#undef AP_DMA_NX
+#undef AP_DMA_HEAD
+
+// The swizzle of the row that lane l handles in load instruction j repeats in j with this period
+// (swz_k and swz_u of a D = 128 tile see 4 rows per instruction and repeat every 16 rows, ...).
+template <int D, int S> constexpr int swz_period() { return S == SWZ_VALUE ? 1 : (D == 128 ? 4 : (D == 64 ? 2 : 1)); }
+constexpr int const_gcd(int a, int b) { return b == 0 ? a : const_gcd(b, a % b); }
+
 // Issue the loads of one 64-row tile (rows row0.. of a [rows, D] bf16 slice described by the
 // buffer resource) into LDS with swizzle S (SWZ_KEY, SWZ_VALUE or SWZ_BOTH).  Every wavefront
-// instruction moves 64 x 16 bytes = 1 KB.
+// instruction moves 64 x 16 bytes = 1 KB; wavefront w issues instructions w, w + NW, ...
 template <int D, int NW, int S>
 __device__ __forceinline__ void issue_tile_loads(rsrc_t rsrc, lds_u16* dst, int row0,
                                                  int stride_bytes, int wave, int lane)
@@ -98,21 +155,23 @@ __device__ __forceinline__ void issue_tile_loads(rsrc_t rsrc, lds_u16* dst, int 
     constexpr int RPI = 64 / CPR;             // rows per wavefront instruction
     constexpr int NI = kBN / RPI;             // instructions per tile
     static_assert(NI % NW == 0, "instructions must divide over the wavefronts");
+    constexpr int N = NI / NW;
+    constexpr int PU = swz_period<D, S>() / const_gcd(swz_period<D, S>(), NW);   // period in u
     const int rl = lane / CPR;                // row inside the instruction
     const int cp = lane % CPR;                // chunk position in LDS
+    int voff[N];
 #pragma unroll
-    for (int u = 0; u < NI / NW; ++u) {
-        const int j = wave + NW * u;
-        const int r = j * RPI + rl;           // row inside the tile
-        const int c = cp ^ swz<D, S>(r);
-        const int voff = rl * stride_bytes + c * 16;
-        const int soff = (row0 + j * RPI) * stride_bytes;
-        load16_to_lds(lds_addr_of(dst + j * 512), voff, rsrc, soff);
+    for (int u = 0; u < N; ++u) {
+        const int r = (wave + NW * (u % PU)) * RPI + rl;      // a row with the swizzle of load u's
+        voff[u] = rl * stride_bytes + (cp ^ swz<D, S>(r)) * 16;
     }
+    load16_chain<N, NW * 1024>(lds_addr_of(dst + wave * 512), (row0 + wave * RPI) * stride_bytes,
+                               NW * RPI * stride_bytes, voff, rsrc);
 }
 
 // Same for a gathered entry: row u of this lane's instructions comes from key gidx[u]
-// (an empty slot holds Lk, which lies beyond num_records and reads as zeros).
+// (an empty slot holds Lk, which lies beyond num_records and reads as zeros).  Keys and the
+// row stride in bytes are below 2^24 (checked by the host), so the full-rate 24-bit multiply serves.
 template <int D, int NW, int S>
 __device__ __forceinline__ void issue_gather_loads(rsrc_t rsrc, lds_u16* dst, const int* gidx,
                                                    int stride_bytes, int wave, int lane)
@@ -120,16 +179,17 @@ __device__ __forceinline__ void issue_gather_loads(rsrc_t rsrc, lds_u16* dst, co
     constexpr int CPR = D / 8;
     constexpr int RPI = 64 / CPR;
     constexpr int NI = kBN / RPI;
+    constexpr int N = NI / NW;
+    constexpr int PU = swz_period<D, S>() / const_gcd(swz_period<D, S>(), NW);
     const int rl = lane / CPR;
     const int cp = lane % CPR;
+    int voff[N];
 #pragma unroll
-    for (int u = 0; u < NI / NW; ++u) {
-        const int j = wave + NW * u;
-        const int r = j * RPI + rl;
-        const int c = cp ^ swz<D, S>(r);
-        const int voff = gidx[u] * stride_bytes + c * 16;
-        load16_to_lds(lds_addr_of(dst + j * 512), voff, rsrc, 0);
+    for (int u = 0; u < N; ++u) {
+        const int r = (wave + NW * (u % PU)) * RPI + rl;
+        voff[u] = (int)__umul24((unsigned)gidx[u], (unsigned)stride_bytes) + (cp ^ swz<D, S>(r)) * 16;
     }
+    load16_chain<N, NW * 1024>(lds_addr_of(dst + wave * 512), 0, 0, voff, rsrc);
 }
 
 // C[64 x 32] = T[64 x D] * R^T[D x 32]: T is a 64-row tile in LDS (rows of D bf16, key swizzle),
