@@ -1,10 +1,13 @@
 // Masked attention forward in fp32 vector arithmetic (Section 3.2, masked-attention equation).
 //
-// One wavefront per 64-query block row; each lane owns one query.  The kernel walks the stored
-// tiles of its block row, stages the tile's 64 key rows and 64 value rows in LDS (coalesced
-// 128-bit loads), and for every key column that any lane keeps it forms the scaled dot product
-// (LDS broadcast reads), masks it with the lane's bitmap bit, and folds it into an online
-// softmax.  This is the fp32 path (and a matrix-core-free cross-check for bf16 storage).
+// One workgroup of four wavefronts per 64-query block row; in every wavefront each lane owns one
+// query, and wavefront w takes the key columns c with c % 4 == w of every tile (interleaved, so a
+// diagonal tile's visible columns spread evenly).  The workgroup walks the stored tiles of its block
+// row, stages the tile's 64 key rows and 64 value rows in LDS (coalesced 128-bit loads), and every
+// wavefront, for each of its key columns that any lane keeps, forms the scaled dot product (LDS
+// broadcast reads), masks it with the lane's bitmap bit, and folds it into an online softmax of its
+// own.  The four partial states (maximum, sum, accumulator) are merged through LDS at the end.
+// This is the fp32 path (and a matrix-core-free cross-check for bf16 storage).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -16,6 +19,7 @@ namespace {
 
 constexpr int kBM = 64;
 constexpr int kBN = 64;
+constexpr int kNW = 4;                                 // wavefronts per block row
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -32,12 +36,12 @@ __device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
 // Load 64 rows x D elements of X (rows row0.., clamped to n_rows-1) into LDS as fp32.
 template <bool BF16, int D>
 __device__ __forceinline__ void stage_rows(float* __restrict__ dst, const void* __restrict__ base,
-                                           long long stride_seq, int row0, int n_rows, int lane)
+                                           long long stride_seq, int row0, int n_rows, int tid)
 {
     constexpr int EPC = BF16 ? 8 : 4;                  // elements per 16-byte chunk
     constexpr int CPR = D / EPC;                       // chunks per row
     constexpr int LSTR = D + 4;                        // LDS row stride in floats
-    for (int c = lane; c < kBN * CPR; c += 64) {
+    for (int c = tid; c < kBN * CPR; c += 64 * kNW) {
         const int r = c / CPR;
         const int e0 = (c % CPR) * EPC;
         int row = row0 + r;
@@ -61,14 +65,20 @@ __device__ __forceinline__ void stage_rows(float* __restrict__ dst, const void* 
 }
 
 template <bool BF16, int D>
-__global__ __launch_bounds__(64) void fwd_valu_kernel(FwdArgs a, int nQB)
+__global__ __launch_bounds__(64 * kNW) void fwd_valu_kernel(FwdArgs a, int nQB)
 {
     constexpr int LSTR = D + 4;
-    __shared__ __attribute__((aligned(16))) float Ks[kBN * LSTR];
-    __shared__ __attribute__((aligned(16))) float Vs[kBN * LSTR];
-    __shared__ float Ss[kBN * 64];                     // [key column][lane]
+    constexpr int STAGE = 2 * kBN * LSTR + kBN * 64;   // floats: key rows, value rows, scores
+    constexpr int MERGE = 2 * (D + 2) * 64;            // two partial states, [state][field][lane]
+    static_assert(MERGE <= STAGE, "the merge buffers reuse the staging area");
+    __shared__ __attribute__((aligned(16))) float smem[STAGE];
+    float* Ks = smem;
+    float* Vs = Ks + kBN * LSTR;
+    float* Ss = Vs + kBN * LSTR;                       // [key column][lane]
 
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qb = nQB - 1 - (int)blockIdx.x;          // long causal rows first
     const int h = blockIdx.y;
     const int b = blockIdx.z;
@@ -125,17 +135,18 @@ __global__ __launch_bounds__(64) void fwd_valu_kernel(FwdArgs a, int nQB)
             if (lim < 0) word = 0;
             else if (lim < 63) word &= (2ull << lim) - 1ull;
         }
+        // every wavefront holds the same 64 queries: the same decision in all four
         if (__ballot(word != 0) == 0) continue;        // nothing visible in this tile
 
         __syncthreads();                               // previous tile's LDS reads are done
-        stage_rows<BF16, D>(Ks, Kp, a.sk[2], k0, a.Lk, lane);
-        stage_rows<BF16, D>(Vs, Vp, a.sv[2], k0, a.Lk, lane);
+        stage_rows<BF16, D>(Ks, Kp, a.sk[2], k0, a.Lk, tid);
+        stage_rows<BF16, D>(Vs, Vp, a.sv[2], k0, a.Lk, tid);
         __syncthreads();
 
-        // scores of this tile; pruned entries stay at -inf
+        // scores of this wavefront's columns; pruned entries stay at -inf
         float tile_max = -INFINITY;
         unsigned long long used = 0;                   // columns some lane keeps (wave-uniform)
-        for (int c = 0; c < kBN; ++c) {
+        for (int c = wave; c < kBN; c += kNW) {
             const bool mine = (word >> c) & 1ull;
             if (__ballot(mine) == 0) continue;
             used |= 1ull << c;
@@ -181,7 +192,35 @@ __global__ __launch_bounds__(64) void fwd_valu_kernel(FwdArgs a, int nQB)
         }
     }
 
-    if (!row_ok) return;
+    // merge the four partial states pairwise through LDS: (1 -> 0, 3 -> 2), then 2 -> 0
+    auto put = [&](int slot) {
+        float* p = smem + slot * (D + 2) * 64 + lane;
+        p[0] = m;
+        p[64] = l;
+#pragma unroll
+        for (int e = 0; e < D; ++e) p[(2 + e) * 64] = acc[e];
+    };
+    auto take = [&](int slot) {
+        const float* p = smem + slot * (D + 2) * 64 + lane;
+        const float m2 = p[0], l2 = p[64];
+        const float m_new = fmaxf(m, m2);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float a1 = __builtin_amdgcn_exp2f(m - m_use), a2 = __builtin_amdgcn_exp2f(m2 - m_use);
+        l = l * a1 + l2 * a2;
+#pragma unroll
+        for (int e = 0; e < D; ++e) acc[e] = acc[e] * a1 + p[(2 + e) * 64] * a2;
+        m = m_new;
+    };
+    __syncthreads();                                   // the staging area is free
+    if (wave & 1) put(wave >> 1);
+    __syncthreads();
+    if (!(wave & 1)) take(wave >> 1);
+    __syncthreads();
+    if (wave == 2) put(0);
+    __syncthreads();
+    if (wave != 0 || !row_ok) return;
+    take(0);
+
     const float inv = l > 0.f ? 1.f / l : 0.f;
     if (BF16) {
         uint16_t* orow = (uint16_t*)Op + (size_t)i * a.so[2];
@@ -210,7 +249,7 @@ template <bool BF16, int D>
 hipError_t launch_one(const FwdArgs& a, hipStream_t stream)
 {
     const int nQB = (a.Lq + kBM - 1) / kBM;
-    hipLaunchKernelGGL((fwd_valu_kernel<BF16, D>), dim3(nQB, a.H, a.B), dim3(64), 0, stream, a, nQB);
+    hipLaunchKernelGGL((fwd_valu_kernel<BF16, D>), dim3(nQB, a.H, a.B), dim3(64 * kNW), 0, stream, a, nQB);
     return hipGetLastError();
 }
 

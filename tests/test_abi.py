@@ -136,6 +136,10 @@ def test_schedule_arguments(L):
     # forward: a schedule needs bf16 and complete pointers
     assert _fwd(L, sched=C.pointer(hole)) == ap.AP_ERR_INVALID_ARG
     assert _fwd(L, sched=C.pointer(good), dtype=ap.AP_F32) == ap.AP_ERR_UNSUPPORTED
+    # gathered rows are addressed with a 24-bit multiply: lengths and row strides in bytes below 2^24
+    wide = (ctypes.c_int64 * 3)(2 * 64 * (1 << 23), 64 * (1 << 23), 1 << 23)
+    assert _fwd(L, sched=C.pointer(good), sk=wide) == ap.AP_ERR_UNSUPPORTED
+    assert _fwd(L, sched=C.pointer(good), Lk=1 << 24, D=32) == ap.AP_ERR_UNSUPPORTED
 
 
 def test_mask_construction_arguments(L):
