@@ -42,12 +42,15 @@ template <int D, int S> __device__ __forceinline__ int swz(int r)
     return S == SWZ_KEY ? swz_k<D>(r) : (S == SWZ_VALUE ? swz_v<D>(r) : swz_u<D>(r));
 }
 
+// two floats -> two bf16 (round to nearest even) in one register: the hardware conversion, one
+// instruction per pair
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
 {
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
