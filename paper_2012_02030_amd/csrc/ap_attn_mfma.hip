@@ -49,8 +49,16 @@ using namespace mfma;
 // SPLIT = true: the entries of a block row are cut into a.splits contiguous chunks, one workgroup
 // each, which write a normalised fp32 partial output and its log-sum-exp for merge_splits_kernel
 // (few queries against many keys: one workgroup per block row would leave the chip idle).
+//
+// The leading scalar arguments repeat fields of `a` (row pointers, entry counts, block rows per head
+// of the layout, heads, splits): the library is built with kernel-argument preloading, which hands
+// the first 16 dwords of the argument block to a wavefront in registers when it starts, so the
+// loads of the block row's pointer and count go out at once instead of after a first round trip
+// for the argument block (the structure itself is too large to be preloaded).
 template <int D, int NW, int STAGES, bool SCHED, bool SPLIT = false>
-__global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd_mfma_kernel(FwdArgs a, int nQB, int xcd_chunk)
+__global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd_mfma_kernel(
+    const int32_t* __restrict__ p_row_ptr, const int32_t* __restrict__ p_cnt, int nQB, int xcd_chunk,
+    int p_nqb_layout, int p_H, int p_splits, FwdArgs a)
 {
     constexpr int BM = 32 * NW;
     constexpr int KSTEPS = D / 16;                           // contraction steps of Q K^T
@@ -82,12 +90,15 @@ __global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd
     if (xcd_chunk > 0) bid = (bid & 7) * xcd_chunk + (bid >> 3);
     int split = 0;
     if (SPLIT) {
-        split = bid % a.splits;
-        bid /= a.splits;
+        split = bid % p_splits;
+        bid /= p_splits;
     }
     const int qb = nQB - 1 - (bid % nQB);                    // long causal rows first
-    const int h = (bid / nQB) % a.H;
-    const int b = bid / (nQB * a.H);
+    const int h = (bid / nQB) % p_H;
+    const int b = bid / (nQB * p_H);
+    const int r = h * p_nqb_layout + qb;                     // requested first: everything else waits for these
+    int t_begin = p_row_ptr[r];
+    int nt = SCHED ? p_cnt[r] : p_row_ptr[r + 1] - t_begin;
 
     const uint16_t* Qp = (const uint16_t*)a.Q + (size_t)b * a.sq[0] + (size_t)h * a.sq[1];
     const uint16_t* Kp = (const uint16_t*)a.K + (size_t)b * a.sk[0] + (size_t)h * a.sk[1];
@@ -120,9 +131,6 @@ __global__ __launch_bounds__(64 * NW, (D <= 64 && STAGES == 1) ? 3 : 2) void fwd
     float lsum = 0.f;                                        // this lane's share of the row sum
     const float sc = a.scale * kLog2e;
 
-    const int r = h * a.nqb_layout + qb;
-    int t_begin = a.row_ptr[r];
-    int nt = SCHED ? a.sched.cnt[r] : a.row_ptr[r + 1] - t_begin;
     if (SPLIT) {                                             // this workgroup's chunk of the entries
         const int chunk = (nt + a.splits - 1) / a.splits;
         const int e0 = min(nt, split * chunk);
@@ -551,12 +559,13 @@ hipError_t launch_one(const FwdArgs& a, hipStream_t stream)
     const int nQB = (a.Lq + 32 * NW - 1) / (32 * NW);
     const long long blocks = (long long)nQB * a.H * a.B;
     const int xcd_chunk = (blocks % 8 == 0) ? (int)(blocks / 8) : 0;
-    if (a.sched.cnt)
-        hipLaunchKernelGGL((fwd_mfma_kernel<D, NW, STAGES, true>), dim3((unsigned)blocks),
-                           dim3(64 * NW), 0, stream, a, nQB, xcd_chunk);
+    const int32_t* cnt = a.sched.cnt;
+    if (cnt)
+        hipLaunchKernelGGL((fwd_mfma_kernel<D, NW, STAGES, true>), dim3((unsigned)blocks), dim3(64 * NW), 0,
+                           stream, a.row_ptr, cnt, nQB, xcd_chunk, a.nqb_layout, a.H, a.splits, a);
     else
-        hipLaunchKernelGGL((fwd_mfma_kernel<D, NW, STAGES, false>), dim3((unsigned)blocks),
-                           dim3(64 * NW), 0, stream, a, nQB, xcd_chunk);
+        hipLaunchKernelGGL((fwd_mfma_kernel<D, NW, STAGES, false>), dim3((unsigned)blocks), dim3(64 * NW), 0,
+                           stream, a.row_ptr, cnt, nQB, xcd_chunk, a.nqb_layout, a.H, a.splits, a);
     return hipGetLastError();
 }
 
@@ -605,12 +614,13 @@ hipError_t launch_split_d(const FwdArgs& a, hipStream_t stream)
     const int nQB = (a.Lq + 63) / 64;
     const long long blocks = (long long)nQB * a.H * a.B * a.splits;
     constexpr int ST = D == 128 ? 1 : 2;
-    if (a.sched.cnt)
+    const int32_t* cnt = a.sched.cnt;
+    if (cnt)
         hipLaunchKernelGGL((fwd_mfma_kernel<D, 2, ST, true, true>), dim3((unsigned)blocks), dim3(128), 0,
-                           stream, a, nQB, 0);
+                           stream, a.row_ptr, cnt, nQB, 0, a.nqb_layout, a.H, a.splits, a);
     else
         hipLaunchKernelGGL((fwd_mfma_kernel<D, 2, ST, false, true>), dim3((unsigned)blocks), dim3(128), 0,
-                           stream, a, nQB, 0);
+                           stream, a.row_ptr, cnt, nQB, 0, a.nqb_layout, a.H, a.splits, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const long long threads = (long long)a.B * a.H * a.Lq * (D / 4);

@@ -65,7 +65,7 @@ __device__ __forceinline__ void stage_rows(float* __restrict__ dst, const void* 
 }
 
 template <bool BF16, int D>
-__global__ __launch_bounds__(64 * kNW) void fwd_valu_kernel(FwdArgs a, int nQB)
+__global__ __launch_bounds__(64 * kNW) void fwd_valu_kernel(const int32_t* __restrict__ p_row_ptr, int nQB, FwdArgs a)
 {
     constexpr int LSTR = D + 4;
     constexpr int STAGE = 2 * kBN * LSTR + kBN * 64;   // floats: key rows, value rows, scores
@@ -82,6 +82,10 @@ __global__ __launch_bounds__(64 * kNW) void fwd_valu_kernel(FwdArgs a, int nQB)
     const int qb = nQB - 1 - (int)blockIdx.x;          // long causal rows first
     const int h = blockIdx.y;
     const int b = blockIdx.z;
+    // the row pointers travel as a leading argument (preloaded into registers at wavefront start),
+    // so this load does not wait for the argument block
+    const int r = h * nQB + qb;
+    const int t_begin = p_row_ptr[r], t_end = p_row_ptr[r + 1];
     const int i = qb * kBM + lane;                     // this lane's query
     const bool row_ok = i < a.Lq;
     const int iq = row_ok ? i : a.Lq - 1;
@@ -122,8 +126,6 @@ __global__ __launch_bounds__(64 * kNW) void fwd_valu_kernel(FwdArgs a, int nQB)
     float m = -INFINITY;                               // running max (log2 domain)
     float l = 0.f;                                     // running sum of 2^(s - m)
 
-    const int r = h * nQB + qb;
-    const int t_begin = a.row_ptr[r], t_end = a.row_ptr[r + 1];
     const long long diag = (long long)i + (a.Lk - a.Lq);   // last visible key if causal
 
     for (int t = t_begin; t < t_end; ++t) {
@@ -249,7 +251,8 @@ template <bool BF16, int D>
 hipError_t launch_one(const FwdArgs& a, hipStream_t stream)
 {
     const int nQB = (a.Lq + kBM - 1) / kBM;
-    hipLaunchKernelGGL((fwd_valu_kernel<BF16, D>), dim3(nQB, a.H, a.B), dim3(64 * kNW), 0, stream, a, nQB);
+    hipLaunchKernelGGL((fwd_valu_kernel<BF16, D>), dim3(nQB, a.H, a.B), dim3(64 * kNW), 0, stream, a.row_ptr,
+                       nQB, a);
     return hipGetLastError();
 }
 

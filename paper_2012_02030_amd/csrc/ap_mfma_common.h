@@ -52,6 +52,16 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
     v[1] = (__bf16)hi;
     return __builtin_bit_cast(uint32_t, v);
 }
+// The same rounding in integer arithmetic (finite inputs).  Used where a kernel sits at its
+// register limit: the compiler converts several pairs ahead of their stores with the form above,
+// and in the layout-walking dK/dV kernel at D = 128 that costs a spilled register.
+__device__ __forceinline__ uint32_t pack_bf16_rne_int(float lo, float hi)
+{
+    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+    a += 0x7fffu + ((a >> 16) & 1u);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (a >> 16) | (b & 0xffff0000u);
+}
 
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -372,8 +382,8 @@ __device__ __forceinline__ void store_rows_bf16(uint16_t* stage, const f32x16* a
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
             uint2 w;
-            w.x = pack_bf16_rne(acc[db][4 * g4] * mul, acc[db][4 * g4 + 1] * mul);
-            w.y = pack_bf16_rne(acc[db][4 * g4 + 2] * mul, acc[db][4 * g4 + 3] * mul);
+            w.x = pack_bf16_rne_int(acc[db][4 * g4] * mul, acc[db][4 * g4 + 1] * mul);
+            w.y = pack_bf16_rne_int(acc[db][4 * g4 + 2] * mul, acc[db][4 * g4 + 3] * mul);
             const int chunk = (4 * db + g4) ^ f;
             *reinterpret_cast<uint2*>(stage + n * D + chunk * 8 + 4 * hh) = w;
         }
