@@ -23,10 +23,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
 INFINITY_CACHE_BYTES = 256 << 20
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the same
-# counters' reading of a plain 256 MiB copy): 261.7 MB read + 68.2 MB written, taken on 2026-11-28 at
-# commit 38194bd; see profiles/fwd_mfma_kernel_C5.md.  Keyed by (workload, block_m, visit schedule
+# counters' reading of a plain 256 MiB copy): 263.2 MB read + 68.2 MB written, taken on 2026-11-28 at
+# commit a175aa2; see profiles/fwd_mfma_kernel_C5.md.  Keyed by (workload, block_m, visit schedule
 # used); other settings report null.
-MEASURED_TRAFFIC_BYTES = {("C5", 64, True): 329.9e6}
+MEASURED_TRAFFIC_BYTES = {("C5", 64, True): 331.4e6}
 
 
 def parse():
@@ -812,7 +812,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": head_res["hbm_gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": head_res["hbm_roofline_frac"],
                      "traffic": MEASURED_TRAFFIC_BYTES.get((head.name, args.block_m, not args.no_sched)),
-                     "traffic_source": "profiles/fwd_mfma_kernel_C5.md (separate rocprofv3 --pmc runs, 2026-11-28, commit 38194bd)",
+                     "traffic_source": "profiles/fwd_mfma_kernel_C5.md (separate rocprofv3 --pmc runs, 2026-11-28, commit a175aa2)",
                      "kernel": "fwd_mfma_kernel" if head.dtype == "bf16" else "fwd_valu_kernel",
                      "algorithmic_bytes_per_launch": head_res["hbm_alg_bytes"]},
         "roofline_dense_run": {"bound": "mfma", "achieved": head_res["dense_tflops"], "peak": MFMA_BF16_PEAK_TFLOPS,
